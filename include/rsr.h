@@ -1,0 +1,150 @@
+/*
+ * librsr -- Redundant Segment Reduction (RSR) matrix-vector multiplication
+ * for binary {0,1} and ternary {-1,0,+1} matrices on AMD MI355X (gfx950).
+ *
+ * C ABI.  Every pointer argument says whether it is a HOST or a DEVICE
+ * pointer.  No function throws or aborts; failures are reported through
+ * return codes and rsr_last_error().  The library is the product: there is no
+ * CPU fallback, and every step listed below runs in HIP kernels.
+ *
+ * Orientation (paper, System Overview): the product is out = M * v with M of
+ * shape rows x cols, v of length cols, out of length rows.  M is split into
+ * horizontal blocks of k rows; inside a block, columns that carry the same
+ * k-entry pattern are grouped, their entries of v are summed once, and every
+ * group sum is distributed once to the block rows its pattern names.
+ */
+#ifndef RSR_H
+#define RSR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rsr_handle_s *rsr_handle_t;
+
+/* kind: what the handle holds */
+enum {
+    RSR_BINARY = 0,           /* M in {0,1}; one pass, 2^k patterns per block            */
+    RSR_TERNARY_2PASS = 1,    /* M = M+ - M-, each half handled as a binary pass          */
+    RSR_TERNARY_FUSED = 2,    /* one pass over base-3 patterns (3^k per block)            */
+    RSR_DENSE_TERNARY_P2 = 3  /* comparison point: dense 2-bit packed ternary, no RSR     */
+};
+
+/* element type of the activation vector v */
+enum { RSR_F32 = 0, RSR_BF16 = 1 };
+
+/* error codes */
+enum {
+    RSR_OK = 0,
+    RSR_EINVAL = 1,       /* null pointer, non-positive size, unknown enum, bad handle     */
+    RSR_EVALUE = 2,       /* a matrix entry is outside the alphabet of the kind            */
+    RSR_EUNSUPPORTED = 3, /* valid request outside the limits stated below                 */
+    RSR_ENOMEM = 4,       /* device or host allocation failed                              */
+    RSR_EHIP = 5,         /* a HIP runtime call failed                                     */
+    RSR_EINTERNAL = 6     /* a self-check of the preprocessing output failed               */
+};
+
+/*
+ * rsr_preprocess -- the one-time offline phase (paper, System Overview,
+ * "Algorithm overview", and Kernels Implementation: counting sort over the
+ * discrete pattern space, compact 16-bit metadata, indices ascending inside
+ * a group, zero-contribution groups dropped).
+ *
+ *   M     DEVICE pointer, int8, row-major [rows][cols]; entries {0,1} for
+ *         RSR_BINARY, {-1,0,+1} otherwise.  Borrowed: the caller keeps
+ *         ownership and may free it as soon as the call returns.
+ *   rows  number of outputs (>= 1); need not be a multiple of k (the last
+ *         block is completed with zero rows, whose outputs are never written)
+ *   cols  length of v, 1 <= cols <= 32766
+ *   k     block height.  RSR_BINARY / RSR_TERNARY_2PASS: 1..15;
+ *         RSR_TERNARY_FUSED: 1..10; in all cases 4*P + 4*(cols+1) + 2 KiB
+ *         must fit the 160 KiB of LDS (P = 2^k or 3^k), else
+ *         RSR_EUNSUPPORTED.  Ignored for RSR_DENSE_TERNARY_P2.
+ *
+ * Pattern code of column j in block b: row b*k+r is digit r, least
+ * significant first; binary digits {0,1} base 2; fused digits 0,1,2 for
+ * 0,+1,-1 base 3.  The handle keeps, per pass, the canonical artifacts
+ * (column permutation pi, group boundaries off; see the getters) and the
+ * compact stream the multiply kernel reads.
+ *
+ * Runs on the current HIP device, on the null stream, and synchronises
+ * before returning.  Returns NULL on failure (see rsr_last_error()).
+ * The handle owns its device buffers until rsr_destroy().
+ */
+rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, int kind);
+
+/*
+ * rsr_matvec -- the online phase (paper, System Overview: aggregate the
+ * entries of v of each group, distribute each group sum once; Kernels
+ * Implementation: gather, aggregate and scatter phases).
+ *
+ *   v      DEVICE pointer, float32 [cols]
+ *   out    DEVICE pointer, float32 [rows]; overwritten (no accumulate)
+ *   stream hipStream_t passed as void*; NULL = the null stream
+ *
+ * Asynchronous on `stream`; allocates nothing and never synchronises, so it
+ * may be captured into a HIP graph.  Calls on different streams with
+ * different `out` may overlap.  Accumulation is float32.
+ */
+int rsr_matvec(rsr_handle_t h, const void *v, void *out, void *stream);
+
+/*
+ * rsr_matvec_ex -- rsr_matvec with a vector type, an output scale and a batch
+ * of independent vectors.
+ *
+ *   v_dtype RSR_F32 or RSR_BF16 (bf16 inputs are widened exactly; accumulation
+ *           and output stay float32)
+ *   scale   per-tensor scale applied to every output
+ *   batch   number of vectors (>= 1); vector i starts at v + i*ldv elements,
+ *           its result at out + i*ldo elements (ldv >= cols, ldo >= rows)
+ */
+int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void *out,
+                  int batch, int64_t ldv, int64_t ldo, void *stream);
+
+/* Frees the handle and its device buffers.  NULL is allowed. */
+void rsr_destroy(rsr_handle_t h);
+
+/* Code of the last failure on the calling thread, and a static description. */
+int rsr_last_error(void);
+const char *rsr_error_string(int code);
+
+/*
+ * Inspection (for parity checks and for the benchmark's byte model).
+ * `pass` is 0 for one-pass kinds; for RSR_TERNARY_2PASS pass 0 is M+ and
+ * pass 1 is M-.  Host buffers are caller-allocated.
+ *
+ *   rsr_get_perm     HOST uint32 [nb][cols]: pi of every block -- columns in
+ *                    ascending pattern code, ascending column inside a group
+ *   rsr_get_offsets  HOST uint32 [nb][P+1]: group c of block b is
+ *                    pi[b][off[b][c] .. off[b][c+1])
+ *   rsr_get_packed   HOST uint8 [rows][ceil(cols/4)] (dense kind only): entry j
+ *                    in bits 2*(j%4).. of byte j/4; 00 = 0, 01 = +1, 11 = -1
+ * Not valid for the other family of kinds: RSR_EINVAL.
+ */
+int rsr_get_perm(rsr_handle_t h, int pass, uint32_t *host_pi);
+int rsr_get_offsets(rsr_handle_t h, int pass, uint32_t *host_off);
+int rsr_get_packed(rsr_handle_t h, uint8_t *host_packed);
+
+int64_t rsr_num_blocks(rsr_handle_t h);   /* nb = ceil(rows/k); 0 for the dense kind */
+int64_t rsr_num_patterns(rsr_handle_t h); /* P per pass; 0 for the dense kind        */
+int rsr_num_passes(rsr_handle_t h);       /* 1 or 2; 0 for the dense kind            */
+
+/*
+ * Bytes one call of rsr_matvec_ex must move between HBM and the chip with
+ * this handle's layout: every weight-side byte the kernel reads once, plus
+ * batch * (cols * sizeof(v element) + rows * 4).  -1 on a bad argument.
+ */
+int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch);
+
+/*
+ * Name of the multiply kernel this handle launches for a vector type (the
+ * symbol a profiler reports), or NULL on a bad argument.  Static storage.
+ */
+const char *rsr_kernel_name(rsr_handle_t h, int v_dtype);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RSR_H */

@@ -1,0 +1,301 @@
+// C ABI of librsr: argument checks, device-memory ownership, and the order of
+// the preprocessing launches.  All arithmetic of the method is in the kernels
+// (rsr_preprocess.hip, rsr_matvec.hip, rsr_dense.hip).
+#include <new>
+#include <vector>
+
+#include "rsr_internal.h"
+
+namespace {
+
+thread_local int g_last_error = RSR_OK;
+
+int fail(int code) {
+    g_last_error = code;
+    return code;
+}
+
+bool good(const rsr_handle_s *h) { return h && h->magic == rsr::kMagic; }
+bool is_rsr_kind(int kind) {
+    return kind == RSR_BINARY || kind == RSR_TERNARY_2PASS || kind == RSR_TERNARY_FUSED;
+}
+
+template <typename T>
+hipError_t dev_alloc(T **p, size_t count) {
+    *p = nullptr;
+    return hipMalloc(reinterpret_cast<void **>(p), count ? count * sizeof(T) : sizeof(T));
+}
+
+void free_handle(rsr_handle_s *h) {
+    if (!h) return;
+    for (auto &ps : h->pass) {
+        if (ps.pi) (void)hipFree(ps.pi);
+        if (ps.off) (void)hipFree(ps.off);
+        if (ps.stream) (void)hipFree(ps.stream);
+        if (ps.hdr) (void)hipFree(ps.hdr);
+    }
+    if (h->packed) (void)hipFree(h->packed);
+    h->magic = 0;
+    delete h;
+}
+
+int64_t ipow(int64_t b, int e) {
+    int64_t p = 1;
+    for (int i = 0; i < e; ++i) p *= b;
+    return p;
+}
+
+// Translate a HIP failure: out-of-memory is reported as such.
+int hip_code(hipError_t e) { return e == hipErrorOutOfMemory ? RSR_ENOMEM : RSR_EHIP; }
+
+#define RSR_TRY(expr)                                   \
+    do {                                                \
+        hipError_t e_ = (expr);                         \
+        if (e_ != hipSuccess) { rc = hip_code(e_); goto done; } \
+    } while (0)
+
+int preprocess_dense(rsr_handle_s *h, const int8_t *M) {
+    int rc = RSR_OK;
+    int *err_flag = nullptr;
+    int host_flag = 0;
+    const int64_t ntiles = (h->cols + 1023) / 1024;
+    h->row_bytes = ntiles * 256;
+    const size_t bytes = (size_t)((h->rows + 3) / 4) * 4 * h->row_bytes;
+    RSR_TRY(dev_alloc(&h->packed, bytes));
+    RSR_TRY(dev_alloc(&err_flag, 1));
+    RSR_TRY(hipMemsetAsync(err_flag, 0, sizeof(int), 0));
+    RSR_TRY(rsr::launch_pack2(M, h->rows, h->cols, h->row_bytes, h->packed, err_flag));
+    RSR_TRY(hipMemcpy(&host_flag, err_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (host_flag) rc = RSR_EVALUE;
+done:
+    if (err_flag) (void)hipFree(err_flag);
+    return rc;
+}
+
+int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
+    int rc = RSR_OK;
+    uint16_t *code = nullptr;
+    uint32_t *lens = nullptr;
+    int *err_flag = nullptr;
+    int host_flag = 0;
+    const int64_t nb = h->nb, cols = h->cols, P = h->P;
+    std::vector<uint32_t> host_lens((size_t)nb);
+    int64_t max_len[2] = {0, 0};
+    static const int modes[3][2] = {{rsr::MODE_BINARY, 0}, {rsr::MODE_POS, rsr::MODE_NEG},
+                                    {rsr::MODE_FUSED3, 0}};
+
+    RSR_TRY(dev_alloc(&code, (size_t)(nb * cols)));
+    RSR_TRY(dev_alloc(&lens, (size_t)nb));
+    RSR_TRY(dev_alloc(&err_flag, 1));
+    RSR_TRY(hipMemsetAsync(err_flag, 0, sizeof(int), 0));
+
+    // encode -> counting sort -> stream length, per pass
+    for (int ps = 0; ps < h->npass; ++ps) {
+        rsr::PassData &pd = h->pass[ps];
+        pd.sign = (ps == 0) ? 1.0f : -1.0f;
+        RSR_TRY(dev_alloc(&pd.pi, (size_t)(nb * cols)));
+        RSR_TRY(dev_alloc(&pd.off, (size_t)(nb * (P + 1))));
+        RSR_TRY(rsr::launch_encode(M, h->rows, cols, h->k, modes[h->kind][ps], code, err_flag));
+        RSR_TRY(rsr::launch_sort(code, nb, cols, h->k, h->base, P, pd.pi, pd.off));
+        RSR_TRY(rsr::launch_stream_len(pd.off, nb, cols, P, lens));
+        RSR_TRY(hipMemcpy(host_lens.data(), lens, (size_t)nb * sizeof(uint32_t),
+                          hipMemcpyDeviceToHost));
+        for (int64_t b = 0; b < nb; ++b)
+            if (host_lens[(size_t)b] > max_len[ps]) max_len[ps] = host_lens[(size_t)b];
+    }
+    RSR_TRY(hipMemcpy(&host_flag, err_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (host_flag) { rc = RSR_EVALUE; goto done; }
+
+    {
+        // Waves per block: about 2048 stream entries (4 iterations) per wave.
+        const int64_t longest = max_len[0] > max_len[1] ? max_len[0] : max_len[1];
+        int W = (int)((longest + 1024) / 2048);
+        if (W < 1) W = 1;
+        if (W > rsr::kMaxWaves) W = rsr::kMaxWaves;
+        h->W = W;
+        const int64_t gran = (int64_t)W * rsr::kChunk;
+        for (int ps = 0; ps < h->npass; ++ps) {
+            rsr::PassData &pd = h->pass[ps];
+            pd.S = (max_len[ps] + gran - 1) / gran * gran;
+            if (pd.S == 0) pd.S = gran;
+            RSR_TRY(dev_alloc(&pd.stream, (size_t)(nb * pd.S)));
+            RSR_TRY(dev_alloc(&pd.hdr, (size_t)(nb * W)));
+            RSR_TRY(rsr::launch_pack_stream(pd.pi, pd.off, nb, cols, P, pd.S, W, pd.stream, pd.hdr,
+                                            err_flag));
+        }
+    }
+    RSR_TRY(hipMemcpy(&host_flag, err_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (host_flag) rc = RSR_EINTERNAL;
+done:
+    if (code) (void)hipFree(code);
+    if (lens) (void)hipFree(lens);
+    if (err_flag) (void)hipFree(err_flag);
+    return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, int kind) {
+    if (!M || rows < 1 || cols < 1 || (!is_rsr_kind(kind) && kind != RSR_DENSE_TERNARY_P2)) {
+        fail(RSR_EINVAL);
+        return nullptr;
+    }
+    if (is_rsr_kind(kind) && k < 1) { fail(RSR_EINVAL); return nullptr; }
+    if (cols > rsr::kMaxCols || rows > (int64_t)1 << 30) { fail(RSR_EUNSUPPORTED); return nullptr; }
+
+    rsr_handle_s *h = new (std::nothrow) rsr_handle_s();
+    if (!h) { fail(RSR_ENOMEM); return nullptr; }
+    h->magic = rsr::kMagic;
+    h->kind = kind;
+    h->rows = rows;
+    h->cols = cols;
+    if (hipGetDevice(&h->device) != hipSuccess) { free_handle(h); fail(RSR_EHIP); return nullptr; }
+
+    int rc;
+    if (kind == RSR_DENSE_TERNARY_P2) {
+        rc = preprocess_dense(h, M);
+    } else {
+        const bool fused = (kind == RSR_TERNARY_FUSED);
+        const int kmax = fused ? 10 : 15;
+        h->k = k;
+        h->base = fused ? 3 : 2;
+        h->npass = (kind == RSR_TERNARY_2PASS) ? 2 : 1;
+        if (k > kmax) { free_handle(h); fail(RSR_EUNSUPPORTED); return nullptr; }
+        h->P = ipow(h->base, k);
+        h->nb = (rows + k - 1) / k;
+        if (rsr::matvec_lds_bytes(h->P, cols, 4) > rsr::kLdsBytes) {
+            free_handle(h);
+            fail(RSR_EUNSUPPORTED);
+            return nullptr;
+        }
+        rc = preprocess_rsr(h, M);
+    }
+    if (rc == RSR_OK && hipDeviceSynchronize() != hipSuccess) rc = RSR_EHIP;
+    if (rc != RSR_OK) {
+        (void)hipGetLastError();
+        free_handle(h);
+        fail(rc);
+        return nullptr;
+    }
+    g_last_error = RSR_OK;
+    return h;
+}
+
+int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void *out, int batch,
+                  int64_t ldv, int64_t ldo, void *stream) {
+    if (!good(h) || !v || !out || batch < 1 || (v_dtype != RSR_F32 && v_dtype != RSR_BF16))
+        return fail(RSR_EINVAL);
+    if (batch > 65535) return fail(RSR_EUNSUPPORTED);
+    if (batch > 1 && (ldv < h->cols || ldo < h->rows)) return fail(RSR_EINVAL);
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    hipError_t e = (h->kind == RSR_DENSE_TERNARY_P2)
+                       ? rsr::launch_dense_matvec(h, v, v_dtype, scale, static_cast<float *>(out),
+                                                  batch, ldv, ldo, s)
+                       : rsr::launch_rsr_matvec(h, v, v_dtype, scale, static_cast<float *>(out),
+                                                batch, ldv, ldo, s);
+    if (e != hipSuccess) return fail(hip_code(e));
+    return RSR_OK;
+}
+
+int rsr_matvec(rsr_handle_t h, const void *v, void *out, void *stream) {
+    if (!good(h)) return fail(RSR_EINVAL);
+    return rsr_matvec_ex(h, v, RSR_F32, 1.0f, out, 1, h->cols, h->rows, stream);
+}
+
+void rsr_destroy(rsr_handle_t h) {
+    if (good(h)) free_handle(h);
+}
+
+int rsr_last_error(void) { return g_last_error; }
+
+const char *rsr_error_string(int code) {
+    switch (code) {
+        case RSR_OK: return "ok";
+        case RSR_EINVAL: return "invalid argument";
+        case RSR_EVALUE: return "matrix entry outside the alphabet of the kind";
+        case RSR_EUNSUPPORTED: return "request outside the supported limits";
+        case RSR_ENOMEM: return "out of memory";
+        case RSR_EHIP: return "HIP runtime error";
+        case RSR_EINTERNAL: return "preprocessing self-check failed";
+        default: return "unknown error";
+    }
+}
+
+int rsr_get_perm(rsr_handle_t h, int pass, uint32_t *host_pi) {
+    if (!good(h) || !host_pi || !is_rsr_kind(h->kind) || pass < 0 || pass >= h->npass)
+        return fail(RSR_EINVAL);
+    const size_t n = (size_t)(h->nb * h->cols);
+    std::vector<uint16_t> tmp(n);
+    if (hipMemcpy(tmp.data(), h->pass[pass].pi, n * sizeof(uint16_t), hipMemcpyDeviceToHost) !=
+        hipSuccess)
+        return fail(RSR_EHIP);
+    for (size_t i = 0; i < n; ++i) host_pi[i] = tmp[i];
+    return RSR_OK;
+}
+
+int rsr_get_offsets(rsr_handle_t h, int pass, uint32_t *host_off) {
+    if (!good(h) || !host_off || !is_rsr_kind(h->kind) || pass < 0 || pass >= h->npass)
+        return fail(RSR_EINVAL);
+    const size_t n = (size_t)(h->nb * (h->P + 1));
+    if (hipMemcpy(host_off, h->pass[pass].off, n * sizeof(uint32_t), hipMemcpyDeviceToHost) !=
+        hipSuccess)
+        return fail(RSR_EHIP);
+    return RSR_OK;
+}
+
+int rsr_get_packed(rsr_handle_t h, uint8_t *host_packed) {
+    if (!good(h) || !host_packed || h->kind != RSR_DENSE_TERNARY_P2) return fail(RSR_EINVAL);
+    const int64_t ntiles = h->row_bytes / 256, ngroups = (h->rows + 3) / 4;
+    const size_t words = (size_t)(ngroups * ntiles * 256);
+    std::vector<uint32_t> tiled(words);
+    if (hipMemcpy(tiled.data(), h->packed, words * 4, hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(RSR_EHIP);
+    // undo the kernel tiling: pure data movement of 2-bit fields
+    const int64_t rb = (h->cols + 3) / 4;
+    for (int64_t i = 0; i < h->rows * rb; ++i) host_packed[i] = 0;
+    for (int64_t i = 0; i < h->rows; ++i) {
+        const int64_t G = i / 4, rr = i % 4;
+        for (int64_t j = 0; j < h->cols; ++j) {
+            const int64_t t = j / 1024, jj = j % 1024;
+            const int64_t i4 = jj / 256, lane = (jj % 256) / 4, s = jj % 4;
+            const uint32_t word = tiled[(size_t)(((G * ntiles + t) * 64 + lane) * 4 + rr)];
+            const uint32_t two = (word >> (2 * (i4 * 4 + s))) & 3u;
+            host_packed[i * rb + j / 4] |= (uint8_t)(two << (2 * (j % 4)));
+        }
+    }
+    return RSR_OK;
+}
+
+int64_t rsr_num_blocks(rsr_handle_t h) { return good(h) ? h->nb : 0; }
+int64_t rsr_num_patterns(rsr_handle_t h) { return good(h) ? h->P : 0; }
+int rsr_num_passes(rsr_handle_t h) { return good(h) ? h->npass : 0; }
+
+int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch) {
+    if (!good(h) || batch < 1 || (v_dtype != RSR_F32 && v_dtype != RSR_BF16)) {
+        fail(RSR_EINVAL);
+        return -1;
+    }
+    const int64_t vb = (v_dtype == RSR_BF16) ? 2 : 4;
+    int64_t weight_side;
+    if (h->kind == RSR_DENSE_TERNARY_P2) {
+        weight_side = (h->rows + 3) / 4 * 4 * h->row_bytes;
+    } else {
+        weight_side = 0;
+        for (int ps = 0; ps < h->npass; ++ps)
+            weight_side += h->nb * (h->pass[ps].S * 2 + (int64_t)h->W * 4);
+    }
+    return weight_side + (int64_t)batch * (h->cols * vb + h->rows * 4);
+}
+
+const char *rsr_kernel_name(rsr_handle_t h, int v_dtype) {
+    if (!good(h) || (v_dtype != RSR_F32 && v_dtype != RSR_BF16)) {
+        fail(RSR_EINVAL);
+        return nullptr;
+    }
+    return h->kind == RSR_DENSE_TERNARY_P2 ? rsr::dense_matvec_kernel_name(v_dtype)
+                                           : rsr::rsr_matvec_kernel_name(h->base, v_dtype);
+}
+
+}  // extern "C"

@@ -1,0 +1,207 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle.  Needs an MI355X.
+
+Bars: pi, group boundaries, packed bytes and integer-valued v: bit-exact.
+float32 / bf16 v: |gpu - oracle| <= 1e-4 * |scale| * sum_j |v_j| per output
+(the oracle accumulates the same, already rounded, inputs in float64).
+"""
+import numpy as np
+import pytest
+
+import oracle
+import rsr_inputs as gen
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+rsr = pytest.importorskip("paper_2603_27462_amd")
+
+KINDS = {rsr.RSR_BINARY: oracle.BINARY, rsr.RSR_TERNARY_2PASS: oracle.TERNARY_2PASS,
+         rsr.RSR_TERNARY_FUSED: oracle.TERNARY_FUSED}
+DEV = "cuda:0"
+
+
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def _bf16_dev(bits):
+    return torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def _matrix(kind, rows, cols, seed, p=0.35):
+    if kind == rsr.RSR_BINARY:
+        return gen.binary_matrix(rows, cols, p, seed)
+    return gen.ternary_matrix(rows, cols, p, seed)
+
+
+def _check_artifacts(h, art):
+    assert rsr.rsr_num_passes(h) == len(art.passes)
+    for n, p in enumerate(art.passes):
+        assert np.array_equal(rsr.rsr_get_perm(h, n), p.pi), "pi differs (pass %d)" % n
+        assert np.array_equal(rsr.rsr_get_offsets(h, n), p.off), "offsets differ (pass %d)" % n
+
+
+def _tol(v, scale=1.0):
+    return 1e-4 * abs(scale) * float(np.abs(v.astype(np.float64)).sum())
+
+
+def _check_matvec(h, M, cols, seed, scale=0.5):
+    # integer-valued v: exact
+    vi = gen.integer_f32(cols, seed=seed)
+    want = oracle.dense_matvec(M, vi.astype(np.float64))
+    got = rsr.rsr_matvec(h, _dev(vi)).cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), want), "integer v not exact"
+    # float32 v, scaled
+    vf = gen.normal_f32(cols, seed=seed + 1)
+    want = oracle.dense_matvec(M, vf.astype(np.float64), scale)
+    got = rsr.rsr_matvec_ex(h, _dev(vf), scale=scale).cpu().numpy()
+    assert np.max(np.abs(got - want)) <= _tol(vf, scale)
+    # bf16 v
+    bits, vals = gen.normal_bf16(cols, seed=seed + 2)
+    want = oracle.dense_matvec(M, vals.astype(np.float64), scale)
+    got = rsr.rsr_matvec_ex(h, _bf16_dev(bits), scale=scale).cpu().numpy()
+    assert np.max(np.abs(got - want)) <= _tol(vals, scale)
+    # determinism: the kernel uses no atomics
+    again = rsr.rsr_matvec_ex(h, _bf16_dev(bits), scale=scale).cpu().numpy()
+    assert np.array_equal(got, again)
+
+
+# shapes span several waves/iterations, ragged column counts and ragged last blocks
+CASES = [
+    # kind, rows, cols, k
+    (rsr.RSR_BINARY, 1024, 1024, 8),          # config 1
+    (rsr.RSR_BINARY, 37, 200, 5),
+    (rsr.RSR_BINARY, 100, 4099, 10),
+    (rsr.RSR_BINARY, 9, 77, 1),
+    (rsr.RSR_BINARY, 33, 9000, 3),            # long groups, several waves
+    (rsr.RSR_BINARY, 64, 513, 12),
+    (rsr.RSR_TERNARY_2PASS, 130, 4096, 4),
+    (rsr.RSR_TERNARY_2PASS, 130, 4096, 6),
+    (rsr.RSR_TERNARY_2PASS, 130, 4096, 8),
+    (rsr.RSR_TERNARY_2PASS, 130, 4096, 10),
+    (rsr.RSR_TERNARY_2PASS, 50, 333, 7),
+    (rsr.RSR_TERNARY_FUSED, 130, 4096, 4),
+    (rsr.RSR_TERNARY_FUSED, 130, 4096, 6),
+    (rsr.RSR_TERNARY_FUSED, 130, 4096, 8),
+    (rsr.RSR_TERNARY_FUSED, 50, 333, 5),
+    (rsr.RSR_TERNARY_FUSED, 22, 14336, 8),    # metric column count
+    (rsr.RSR_TERNARY_FUSED, 20, 2560, 9),
+    (rsr.RSR_TERNARY_FUSED, 7, 31, 2),
+    (rsr.RSR_TERNARY_FUSED, 5, 20001, 7),
+]
+
+
+@pytest.mark.parametrize("kind,rows,cols,k", CASES)
+def test_rsr_parity(kind, rows, cols, k):
+    seed = 1000 + rows + cols + k
+    M = _matrix(kind, rows, cols, seed)
+    h = rsr.rsr_preprocess(_dev(M), k, kind)
+    art = oracle.preprocess(M, k, KINDS[kind])
+    _check_artifacts(h, art)
+    _check_matvec(h, M, cols, seed)
+    rsr.rsr_destroy(h)
+
+
+@pytest.mark.parametrize("kind", [rsr.RSR_BINARY, rsr.RSR_TERNARY_2PASS, rsr.RSR_TERNARY_FUSED])
+def test_degenerate_matrices(kind):
+    rows, cols, k = 21, 1500, 4
+    for name, M in [("zeros", np.zeros((rows, cols), np.int8)),
+                    ("ones", np.ones((rows, cols), np.int8)),
+                    ("minus_ones", -np.ones((rows, cols), np.int8)),
+                    ("one_column", np.zeros((rows, 1), np.int8) + 1),
+                    ("one_row", _matrix(kind, 1, cols, 3))]:
+        if kind == rsr.RSR_BINARY and name == "minus_ones":
+            continue
+        h = rsr.rsr_preprocess(_dev(M), k, kind)
+        _check_artifacts(h, oracle.preprocess(M, k, KINDS[kind]))
+        _check_matvec(h, M, M.shape[1], 7)
+
+
+def test_block_height_exceeds_rows():
+    M = _matrix(rsr.RSR_TERNARY_FUSED, 3, 700, 9)
+    h = rsr.rsr_preprocess(_dev(M), 8, rsr.RSR_TERNARY_FUSED)
+    _check_artifacts(h, oracle.preprocess(M, 8, oracle.TERNARY_FUSED))
+    _check_matvec(h, M, 700, 11)
+
+
+def test_widest_supported_vector():
+    cols = 32766
+    M = _matrix(rsr.RSR_TERNARY_2PASS, 12, cols, 21)
+    h = rsr.rsr_preprocess(_dev(M), 6, rsr.RSR_TERNARY_2PASS)
+    _check_artifacts(h, oracle.preprocess(M, 6, oracle.TERNARY_2PASS))
+    _check_matvec(h, M, cols, 13)
+
+
+def test_batch_and_strides():
+    rows, cols, k = 96, 4096, 8
+    M = _matrix(rsr.RSR_TERNARY_FUSED, rows, cols, 31)
+    h = rsr.rsr_preprocess(_dev(M), k, rsr.RSR_TERNARY_FUSED)
+    vs = np.stack([gen.to_bf16(gen.normal_f32(cols, seed=50 + i))[0] for i in range(4)])
+    vals = (vs.astype(np.uint32) << 16).view(np.float32)
+    vbuf = torch.zeros((4, cols + 64), dtype=torch.bfloat16, device=DEV)     # ldv > cols
+    vbuf[:, :cols] = _bf16_dev(vs)
+    out = torch.full((4, rows + 8), 777.0, dtype=torch.float32, device=DEV)  # ldo > rows
+    rsr.rsr_matvec_ex(h, vbuf[:, :cols], scale=2.0, out=out[:, :rows])
+    got = out.cpu().numpy()
+    assert np.all(got[:, rows:] == 777.0)                                     # nothing past rows
+    for i in range(4):
+        want = oracle.dense_matvec(M, vals[i].astype(np.float64), 2.0)
+        assert np.max(np.abs(got[i, :rows] - want)) <= _tol(vals[i], 2.0)
+
+
+def test_second_stream():
+    rows, cols = 64, 2048
+    M = _matrix(rsr.RSR_BINARY, rows, cols, 41)
+    h = rsr.rsr_preprocess(_dev(M), 8, rsr.RSR_BINARY)
+    vi = gen.integer_f32(cols, seed=5)
+    v = _dev(vi)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    out = rsr.rsr_matvec(h, v, stream=s)
+    s.synchronize()
+    assert np.array_equal(out.cpu().numpy().astype(np.float64),
+                          oracle.dense_matvec(M, vi.astype(np.float64)))
+
+
+# ------------------------------------------------------------ dense comparison kernel
+@pytest.mark.parametrize("rows,cols", [(64, 1024), (37, 333), (130, 4096), (9, 2561), (22, 14336)])
+def test_dense_packed_parity(rows, cols):
+    M = gen.ternary_matrix(rows, cols, 0.35, rows + cols)
+    h = rsr.rsr_preprocess(_dev(M), 0, rsr.RSR_DENSE_TERNARY_P2)
+    assert np.array_equal(rsr.rsr_get_packed(h), oracle.pack2(M))
+    _check_matvec(h, M, cols, rows)
+
+
+# ------------------------------------------------------------------- error behaviour
+def test_errors():
+    M = _dev(gen.ternary_matrix(16, 64, 0.3, 1))
+    with pytest.raises(rsr.RsrError) as e:
+        rsr.rsr_preprocess(M, 4, rsr.RSR_BINARY)          # -1 entries in a binary matrix
+    assert e.value.code == 2
+    with pytest.raises(rsr.RsrError) as e:
+        rsr.rsr_preprocess(M, 11, rsr.RSR_TERNARY_FUSED)  # k beyond the fused limit
+    assert e.value.code == 3
+    with pytest.raises(rsr.RsrError) as e:
+        rsr.rsr_preprocess(M, 10, rsr.RSR_TERNARY_FUSED)  # 3^10 bins do not fit LDS
+    assert e.value.code == 3
+    with pytest.raises(rsr.RsrError) as e:
+        rsr.rsr_preprocess(M, 0, rsr.RSR_TERNARY_2PASS)
+    assert e.value.code == 1
+    with pytest.raises(rsr.RsrError) as e:
+        rsr.rsr_preprocess(M, 4, 9)
+    assert e.value.code == 1
+    bad = _dev(np.full((4, 8), 2, np.int8))
+    with pytest.raises(rsr.RsrError) as e:
+        rsr.rsr_preprocess(bad, 0, rsr.RSR_DENSE_TERNARY_P2)
+    assert e.value.code == 2
+    wide = torch.zeros((2, 32767), dtype=torch.int8, device=DEV)
+    with pytest.raises(rsr.RsrError) as e:
+        rsr.rsr_preprocess(wide, 4, rsr.RSR_BINARY)
+    assert e.value.code == 3
+    h = rsr.rsr_preprocess(M, 4, rsr.RSR_TERNARY_FUSED)
+    with pytest.raises(rsr.RsrError):
+        rsr.rsr_get_packed(h)
+    with pytest.raises(rsr.RsrError):
+        rsr.rsr_get_perm(h, 1)
+    # the library keeps working after errors
+    _check_matvec(h, M.cpu().numpy(), 64, 3)
