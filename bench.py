@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the RSR matvec hot path on one MI355X.
+
+A step is one full pass of the online hot path (gather v through the column
+permutation, aggregate per group, distribute) for the metric workload: a
+ternary 4096 x 14336 matrix (P(0)=0.35, P(+1)=P(-1)=0.325), one bf16 vector,
+float32 output.  Preprocessing is done once before the timed region; all
+handles, vectors and outputs are resident in HBM when timing starts.
+
+Timed region: K launches back to back on one stream inside one HIP graph,
+bracketed by HIP events and device synchronisation.  Launch i uses weight
+set i mod H, with H distinct preprocessed matrices whose streams together
+exceed twice the 256 MB Infinity Cache, so every launch streams its weights
+from HBM ("cold"); the same loop on a single weight set ("warm", cache
+resident) and the dense packed-2-bit comparison kernel are reported as
+extra fields.  One JSON line is printed.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+COLD_WORKING_SET = 600e6      # bytes of distinct weight streams cycled through
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=4000)
+    ap.add_argument("--warmup", type=int, default=400)
+    ap.add_argument("--k", type=int, default=8)
+    ap.add_argument("--kind", default="fused", choices=["fused", "2pass"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip warm and dense legs")
+    ap.add_argument("--sets", type=int, default=0, help="weight sets to cycle (0 = from size)")
+    return ap.parse_args()
+
+
+def time_graph(torch, launch_fn, steps, warmup):
+    """Capture `steps` launches into one HIP graph; return ms for the timed replay."""
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for i in range(min(warmup, 64)):     # eager warm-up (also sets kernel attributes)
+            launch_fn(i, stream)
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(steps):
+                launch_fn(i, stream)
+        # untimed warm-up launches through the same path
+        reps = max(1, (warmup + steps - 1) // steps)
+        for _ in range(reps):
+            graph.replay()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t0 = torch.cuda.Event(enable_timing=True)
+        t1 = torch.cuda.Event(enable_timing=True)
+        t0.record(stream)
+        graph.replay()
+        t1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        return t0.elapsed_time(t1)
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (blocks shard without communication; "
+              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import rsr_inputs as gen
+    import paper_2603_27462_amd as rsr
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    rsr.load_library()
+
+    layer = gen.METRIC_LAYER
+    rows, cols = layer.rows, layer.cols
+    kind = rsr.RSR_TERNARY_FUSED if args.kind == "fused" else rsr.RSR_TERNARY_2PASS
+
+    # ---- inputs (seeded, synthetic) and one-time preprocessing --------------------
+    M0 = gen.metric_matrix()
+    bits, vals = gen.normal_bf16(cols, seed=gen.BASE_SEED + 41)
+    v = torch.from_numpy(bits.view(np.int16)).to(dev).view(torch.bfloat16)
+    t_pre = time.time()
+    h0 = rsr.rsr_preprocess(torch.from_numpy(M0).to(dev), args.k, kind)
+    torch.cuda.synchronize()
+    t_pre = time.time() - t_pre
+    alg_bytes = rsr.rsr_algorithmic_bytes(h0, rsr.RSR_BF16, 1)
+    nsets = args.sets or int(np.ceil(COLD_WORKING_SET / alg_bytes))
+    handles = [h0]
+    for i in range(1, nsets):
+        Mi = gen.ternary_matrix(rows, cols, gen.LLM_8B_P_ZERO, gen.BASE_SEED + 1000 + i)
+        handles.append(rsr.rsr_preprocess(torch.from_numpy(Mi).to(dev), args.k, kind))
+        del Mi
+    outs = torch.zeros((nsets, rows), dtype=torch.float32, device=dev)
+
+    # correctness of the timed configuration against the float64 definition
+    import oracle
+    want = oracle.dense_matvec(M0, vals.astype(np.float64))
+    got = rsr.rsr_matvec_ex(h0, v).cpu().numpy()
+    max_err = float(np.max(np.abs(got - want)))
+    tol = 1e-4 * float(np.abs(vals.astype(np.float64)).sum())
+    if not max_err <= tol:
+        print("bench.py: GPU result outside tolerance (%g > %g)" % (max_err, tol), file=sys.stderr)
+        sys.exit(1)
+
+    def cold(i, s):
+        j = i % nsets
+        rsr.rsr_matvec_ex(handles[j], v, out=outs[j], stream=s)
+
+    def warm(i, s):
+        rsr.rsr_matvec_ex(h0, v, out=outs[0], stream=s)
+
+    ms = time_graph(torch, cold, args.steps, args.warmup)
+    us_per_step = ms * 1e3 / args.steps
+    result = {
+        "metric": "ternary matvec/s + effective HBM GB/s (% of peak), 4096x14336, batch 1",
+        "value": args.steps / (ms * 1e-3),
+        "unit": "matvec/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "ternary 4096x14336 (P0=0.35), bf16 v, batch 1, RSR %s k=%d, "
+                               "%d weight sets cycled (cold, %.0f MB)" %
+                               (args.kind, args.k, nsets, nsets * alg_bytes / 1e6),
+                   "rows": rows, "cols": cols, "k": args.k, "kind": args.kind, "batch": 1,
+                   "v_dtype": "bf16", "weight_sets": nsets},
+    }
+    achieved = alg_bytes / (us_per_step * 1e-6) / 1e9
+    dense_equiv_bytes = rows * cols // 4 + cols * 2 + rows * 4
+    result["roofline"] = {
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+        "kernel": rsr.rsr_kernel_name(h0, rsr.RSR_BF16),
+        "algorithmic_bytes_per_launch": alg_bytes,
+        "avg_launch_us": us_per_step,
+        "dense_equivalent_GBs": dense_equiv_bytes / (us_per_step * 1e-6) / 1e9,
+    }
+    traffic_file = os.path.join(ROOT, "profiles", "traffic_rsr_metric.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            t = json.load(f)
+        if t.get("k") == args.k and t.get("kind") == args.kind:
+            result["roofline"]["traffic"] = t.get("hbm_bytes_per_launch")
+    result["max_abs_err_vs_f64"] = max_err
+    result["tolerance"] = tol
+    result["preprocess_s"] = t_pre
+
+    if not args.no_extras:
+        ms_w = time_graph(torch, warm, args.steps, args.warmup)
+        result["warm"] = {"matvec_per_s": args.steps / (ms_w * 1e-3),
+                          "us_per_step": ms_w * 1e3 / args.steps,
+                          "note": "single weight set, Infinity-Cache resident: not an HBM figure"}
+        # dense packed-2-bit comparison kernel, same protocol
+        dsets = int(np.ceil(COLD_WORKING_SET / dense_equiv_bytes))
+        for hh in handles[1:]:
+            rsr.rsr_destroy(hh)
+        handles[:] = [h0]
+        dh = [rsr.rsr_preprocess(torch.from_numpy(M0).to(dev), 0, rsr.RSR_DENSE_TERNARY_P2)]
+        for i in range(1, dsets):
+            Mi = gen.ternary_matrix(rows, cols, gen.LLM_8B_P_ZERO, gen.BASE_SEED + 1000 + i)
+            dh.append(rsr.rsr_preprocess(torch.from_numpy(Mi).to(dev), 0, rsr.RSR_DENSE_TERNARY_P2))
+            del Mi
+        douts = torch.zeros((dsets, rows), dtype=torch.float32, device=dev)
+        gd = rsr.rsr_matvec_ex(dh[0], v).cpu().numpy()
+        derr = float(np.max(np.abs(gd - want)))
+
+        def dcold(i, s):
+            j = i % dsets
+            rsr.rsr_matvec_ex(dh[j], v, out=douts[j], stream=s)
+
+        def dwarm(i, s):
+            rsr.rsr_matvec_ex(dh[0], v, out=douts[0], stream=s)
+
+        ms_d = time_graph(torch, dcold, args.steps, args.warmup)
+        ms_dw = time_graph(torch, dwarm, args.steps, args.warmup)
+        dbytes = rsr.rsr_algorithmic_bytes(dh[0], rsr.RSR_BF16, 1)
+        result["dense_packed2"] = {
+            "matvec_per_s": args.steps / (ms_d * 1e-3), "us_per_step": ms_d * 1e3 / args.steps,
+            "GBs": dbytes / (ms_d * 1e-3 / args.steps) / 1e9,
+            "warm_us_per_step": ms_dw * 1e3 / args.steps,
+            "weight_sets": dsets, "max_abs_err_vs_f64": derr,
+            "kernel": rsr.rsr_kernel_name(dh[0], rsr.RSR_BF16),
+        }
+        result["speedup_vs_dense_packed2"] = ms_d / ms
+
+    if not args.no_cpu_baseline:
+        # the oracle as it stands (plain C, one thread, float64), on the host cores
+        v64 = vals.astype(np.float64)
+        t0 = time.time()
+        n = 0
+        while time.time() - t0 < 10.0:
+            oracle.dense_matvec(M0, v64)
+            n += 1
+        dt = time.time() - t0
+        art = oracle.preprocess(M0, args.k, oracle.TERNARY_FUSED if args.kind == "fused"
+                                else oracle.TERNARY_2PASS)
+        t1 = time.time()
+        n2 = 0
+        while time.time() - t1 < 5.0:
+            oracle.matvec(art, v64)
+            n2 += 1
+        dt2 = time.time() - t1
+        result["cpu_baseline"] = {
+            "value": n / dt, "unit": "matvec/s", "cores": 1, "kind": "oracle",
+            "sample": "%d full 4096x14336 matvecs by the definition (oracle dense, float64, "
+                      "1 thread) in %.1f s; oracle RSR matvec: %.2f matvec/s; host has %d cpus"
+                      % (n, dt, n2 / dt2, os.cpu_count() or 0),
+        }
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
