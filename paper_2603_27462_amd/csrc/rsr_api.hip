@@ -31,9 +31,11 @@ void free_handle(rsr_handle_s *h) {
     for (auto &ps : h->pass) {
         if (ps.pi) (void)hipFree(ps.pi);
         if (ps.off) (void)hipFree(ps.off);
-        if (ps.stream) (void)hipFree(ps.stream);
-        if (ps.hdr) (void)hipFree(ps.hdr);
+        if (ps.entries) (void)hipFree(ps.entries);
+        if (ps.codes) (void)hipFree(ps.codes);
+        if (ps.wsign) (void)hipFree(ps.wsign);
     }
+    if (h->ftab) (void)hipFree(h->ftab);
     if (h->packed) (void)hipFree(h->packed);
     h->magic = 0;
     delete h;
@@ -74,7 +76,7 @@ done:
 
 int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
     int rc = RSR_OK;
-    uint16_t *code = nullptr;
+    uint16_t *code = nullptr, *scratch = nullptr;
     uint32_t *lens = nullptr;
     int *err_flag = nullptr;
     int host_flag = 0;
@@ -107,27 +109,39 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
     if (host_flag) { rc = RSR_EVALUE; goto done; }
 
     {
-        // Waves per block: about 2048 stream entries (4 iterations) per wave.
         const int64_t longest = max_len[0] > max_len[1] ? max_len[0] : max_len[1];
-        int W = (int)((longest + 1024) / 2048);
-        if (W < 1) W = 1;
-        if (W > rsr::kMaxWaves) W = rsr::kMaxWaves;
-        h->W = W;
-        const int64_t gran = (int64_t)W * rsr::kChunk;
+        rsr::choose_launch_shape(longest, &h->H, &h->W);
+        if (h->W < rsr::min_waves_for_rows(h->k)) h->W = rsr::min_waves_for_rows(h->k);
+        h->enc = (cols <= rsr::kSmallCols) ? rsr::kEncSmall : rsr::kEncBig;
+        const int64_t chunk = (int64_t)rsr::kLoad * h->H;
+        int64_t maxS = 0;
         for (int ps = 0; ps < h->npass; ++ps) {
             rsr::PassData &pd = h->pass[ps];
-            pd.S = (max_len[ps] + gran - 1) / gran * gran;
-            if (pd.S == 0) pd.S = gran;
-            RSR_TRY(dev_alloc(&pd.stream, (size_t)(nb * pd.S)));
-            RSR_TRY(dev_alloc(&pd.hdr, (size_t)(nb * W)));
-            RSR_TRY(rsr::launch_pack_stream(pd.pi, pd.off, nb, cols, P, pd.S, W, pd.stream, pd.hdr,
-                                            err_flag));
+            pd.C = (max_len[ps] + chunk - 1) / chunk;
+            if (pd.C < 1) pd.C = 1;
+            if (pd.C * chunk > maxS) maxS = pd.C * chunk;
+        }
+        const int64_t chunks[2] = {h->pass[0].C, h->pass[1].C};
+        rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
+        RSR_TRY(dev_alloc(&h->ftab, (size_t)h->fold.nrows * 16));
+        RSR_TRY(rsr::launch_fold_tables(h->base, h->k, h->fold, h->ftab));
+        RSR_TRY(dev_alloc(&scratch, (size_t)(nb * maxS)));
+        for (int ps = 0; ps < h->npass; ++ps) {
+            rsr::PassData &pd = h->pass[ps];
+            RSR_TRY(dev_alloc(&pd.entries, (size_t)(nb * pd.C * chunk)));
+            RSR_TRY(dev_alloc(&pd.codes, (size_t)(nb * pd.C * 64)));
+            RSR_TRY(dev_alloc(&pd.wsign, (size_t)(nb * h->W * 16)));
+            RSR_TRY(rsr::launch_pack_stream(pd.pi, pd.off, nb, cols, P, pd.C, h->H, h->enc, scratch,
+                                            pd.entries, pd.codes, err_flag));
+            RSR_TRY(rsr::launch_wave_signs(h->base, h->k, pd.codes, nb, pd.C, h->W, h->fold, ps,
+                                           pd.wsign));
         }
     }
     RSR_TRY(hipMemcpy(&host_flag, err_flag, sizeof(int), hipMemcpyDeviceToHost));
     if (host_flag) rc = RSR_EINTERNAL;
 done:
     if (code) (void)hipFree(code);
+    if (scratch) (void)hipFree(scratch);
     if (lens) (void)hipFree(lens);
     if (err_flag) (void)hipFree(err_flag);
     return rc;
@@ -284,7 +298,9 @@ int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch) {
     } else {
         weight_side = 0;
         for (int ps = 0; ps < h->npass; ++ps)
-            weight_side += h->nb * (h->pass[ps].S * 2 + (int64_t)h->W * 4);
+            weight_side += h->nb * (h->pass[ps].C * ((int64_t)rsr::kLoad * h->H * 2 + 64 * 2) +
+                                    (int64_t)h->W * 16);
+        weight_side += (int64_t)h->fold.nrows * 16;
     }
     return weight_side + (int64_t)batch * (h->cols * vb + h->rows * 4);
 }
@@ -295,7 +311,7 @@ const char *rsr_kernel_name(rsr_handle_t h, int v_dtype) {
         return nullptr;
     }
     return h->kind == RSR_DENSE_TERNARY_P2 ? rsr::dense_matvec_kernel_name(v_dtype)
-                                           : rsr::rsr_matvec_kernel_name(h->base, v_dtype);
+                                           : rsr::rsr_matvec_kernel_name(v_dtype, h->H, h->enc, h->npass);
 }
 
 }  // extern "C"

@@ -9,28 +9,52 @@
 namespace rsr {
 
 constexpr int kMaxWaves = 16;          // waves per workgroup in the multiply kernel
-constexpr int kChunk = 512;            // stream entries one wave consumes per iteration
-constexpr int kMaxCols = 32766;        // index 'cols' is the zero slot; entry = idx<<1|tail
+constexpr int kLoad = 512;             // stream entries one 16-byte-per-lane wave load covers
+constexpr int kMaxCols = 32766;        // index 'cols' is the zero slot and must fit 15 bits
+constexpr int kSmallCols = 16383;      // up to here an entry is tail<<15 | idx<<1
 constexpr int kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
-constexpr int kLdsMisc = 2048;         // wave totals, partial outputs, wave start codes
+constexpr int kLdsMisc = 2048;         // wave-total terms and wave partials of the scatter phase
 
 // One pass of an RSR handle (binary, M+, M- or fused).
+//
+// Multiply-kernel stream of a block: C chunks of 64*8*H entries.  In stream
+// order a chunk is 64 strips of 8*H consecutive entries, strip l belonging to
+// lane l; in memory it is H slabs of 512 entries, slab h holding entries
+// 8h..8h+7 of every strip, lane after lane, so that each of the H loads of a
+// wave is one contiguous 1 KiB read.  codes[chunk][l] is the group code of the
+// first tail entry at or after the start of strip l.
 struct PassData {
-    uint16_t *pi = nullptr;      // canonical column permutation  [nb][cols]
-    uint32_t *off = nullptr;     // canonical group boundaries    [nb][P+1]
-    uint16_t *stream = nullptr;  // multiply-kernel stream        [nb][S]
-    uint32_t *hdr = nullptr;     // first group code of each wave [nb][W]
-    int64_t S = 0;               // stream entries per block (multiple of W*kChunk)
+    uint16_t *pi = nullptr;       // canonical column permutation  [nb][cols]
+    uint32_t *off = nullptr;      // canonical group boundaries    [nb][P+1]
+    uint16_t *entries = nullptr;  // [nb][C][H][64][8]
+    uint16_t *codes = nullptr;    // [nb][C][64]
+    int8_t *wsign = nullptr;      // [nb][W][16]: weight of wave w's total in output row r
+    int64_t C = 0;                // chunks per block
     float sign = 1.0f;
+};
+
+// Launch-time constants of the scatter phase and the split of chunks over waves.
+struct FoldShape {
+    int m = 0, Tc = 0, Q = 0;   // Tc = base^m classes handled by stage 1, Q = P / Tc
+    int parts = 1;              // threads sharing one class in stage 1 (1..4)
+    int ib[5] = {0, 0, 0, 0, 0};
+    int nact = 0;               // waves that hold fold threads
+    int nrows = 0;              // rows of the weight table: max(Tc, Q)
+    unsigned short cb[2][kMaxWaves + 1] = {};  // per pass: wave w owns chunks [cb[w], cb[w+1])
 };
 
 }  // namespace rsr
 
 struct rsr_handle_s {
     uint32_t magic = 0;
-    int kind = 0, k = 0, base = 0, npass = 0, W = 0, device = 0;
+    int kind = 0, k = 0, base = 0, npass = 0, device = 0;
+    int W = 0;    // waves per workgroup of the multiply kernel
+    int H = 0;    // 16-byte loads per lane per chunk (1, 2 or 4)
+    int enc = 0;  // entry encoding: kEncSmall or kEncBig
     int64_t rows = 0, cols = 0, nb = 0, P = 0;
     rsr::PassData pass[2];
+    rsr::FoldShape fold;
+    int8_t *ftab = nullptr;      // scatter weights [fold.nrows][16]
     uint8_t *packed = nullptr;   // dense kind: [rows][row_bytes], row_bytes % 16 == 0
     int64_t row_bytes = 0;
 };
@@ -38,6 +62,11 @@ struct rsr_handle_s {
 namespace rsr {
 
 constexpr uint32_t kMagic = 0x52535231u;
+
+// Entry encodings.  Small (cols <= kSmallCols): tail<<15 | idx<<1, so the LDS
+// byte address of a bf16 element is one AND away and the tail flag is the sign
+// of the 16-bit entry.  Big: idx<<1 | tail.
+enum { kEncSmall = 0, kEncBig = 1 };
 
 // mode of an encode pass
 enum { MODE_BINARY = 0, MODE_POS = 1, MODE_NEG = 2, MODE_FUSED3 = 3 };
@@ -50,8 +79,8 @@ hipError_t launch_sort(const uint16_t *code, int64_t nb, int64_t cols, int k, in
 hipError_t launch_stream_len(const uint32_t *off, int64_t nb, int64_t cols, int64_t P,
                              uint32_t *lens);
 hipError_t launch_pack_stream(const uint16_t *pi, const uint32_t *off, int64_t nb, int64_t cols,
-                              int64_t P, int64_t S, int W, uint16_t *stream, uint32_t *hdr,
-                              int *err_flag);
+                              int64_t P, int64_t C, int H, int enc, uint16_t *scratch,
+                              uint16_t *entries, uint16_t *codes, int *err_flag);
 hipError_t launch_pack2(const int8_t *M, int64_t rows, int64_t cols, int64_t row_bytes,
                         uint8_t *packed, int *err_flag);
 
@@ -60,8 +89,21 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
                              float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
 hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale,
                                float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
-const char *rsr_matvec_kernel_name(int base, int v_dtype);
+const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass);
 const char *dense_matvec_kernel_name(int v_dtype);
+
+// Picks the chunk size (H loads of 512 entries per wave) and the number of
+// waves per workgroup for blocks whose longest stream has `longest` entries.
+// The environment variables RSR_H and RSR_W override the choice (tuning only).
+void choose_launch_shape(int64_t longest, int *H, int *W);
+// The last step of the multiply kernel uses 16 threads per output row of a block.
+int min_waves_for_rows(int k);
+
+void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int npass,
+                     FoldShape *fs);
+hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int8_t *ftab);
+hipError_t launch_wave_signs(int base, int k, const uint16_t *codes, int64_t nb, int64_t C, int W,
+                             const FoldShape &fs, int pass, int8_t *wsign);
 
 // LDS bytes the RSR multiply kernel needs for a pass layout and vector type.
 inline int64_t matvec_lds_bytes(int64_t P, int64_t cols, int v_elem_bytes) {

@@ -5,9 +5,10 @@
 //                digit group by digit group (each pass is a counting sort over
 //                4 or 9 buckets: count, scan, stable placement), then the group
 //                boundaries over all P codes
-//   stream_len / pack_stream
+//   stream_len / pack_stream / finalize_stream
 //                the compact stream the multiply kernel reads: 16-bit entries,
-//                zero-contribution group dropped, one tail flag per group
+//                zero-contribution group dropped, one tail flag per group,
+//                laid out for coalesced per-lane strips
 #include "rsr_internal.h"
 
 namespace rsr {
@@ -207,28 +208,41 @@ __global__ __launch_bounds__(kThreads) void k_pack_stream(const uint16_t *__rest
     }
 }
 
-// hdr[b][w] = code of the first tail at or after the start of wave w's share
-// of the stream = 1 + number of tails before it.  Derived from the stream
-// itself; also checks that the block holds exactly P-1 tails.
-__global__ __launch_bounds__(kThreads) void k_stream_hdr(const uint16_t *__restrict__ stream,
-                                                         int64_t nb, int64_t P, int64_t S, int W,
-                                                         uint32_t *__restrict__ hdr,
-                                                         int *__restrict__ err_flag) {
-    __shared__ uint32_t tails[kMaxWaves];
-    const int64_t share = S / W;
+// Final layout of the stream (see PassData): re-encodes the entries, moves
+// them to the lane-major slabs, and records for every lane strip the group
+// code of the first tail at or after its start (1 + tails before it).  Also
+// checks that the block holds exactly P-1 tails.
+__global__ __launch_bounds__(kThreads) void k_finalize_stream(
+    const uint16_t *__restrict__ logical, int64_t nb, int64_t P, int64_t C, int H, int enc,
+    uint16_t *__restrict__ entries, uint16_t *__restrict__ codes, int *__restrict__ err_flag) {
+    __shared__ uint32_t wsum[kWaves];
+    const int epl = 8 * H;
+    const int64_t S = C * 64 * epl;
+    const int64_t strips = C * 64;
     for (int64_t b = blockIdx.x; b < nb; b += gridDim.x) {
-        const uint16_t *sb = stream + b * S;
-        if (threadIdx.x < kMaxWaves) tails[threadIdx.x] = 0;
-        __syncthreads();
-        for (int64_t t = threadIdx.x; t < S; t += kThreads)
-            if (sb[t] & 1) atomicAdd(&tails[t / share], 1u);
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            uint32_t run = 1;
-            for (int w = 0; w < W; ++w) { hdr[b * W + w] = run; run += tails[w]; }
-            if ((int64_t)run != P) atomicOr(err_flag, 2);
+        const uint16_t *lb = logical + b * S;
+        uint32_t carry = 1;
+        for (int64_t g0 = 0; g0 < strips; g0 += kThreads) {
+            const int64_t g = g0 + threadIdx.x;
+            uint32_t cnt = 0;
+            if (g < strips)
+                for (int i = 0; i < epl; ++i) cnt += lb[g * epl + i] & 1u;
+            uint32_t total;
+            const uint32_t ex = wg_exclusive_scan(cnt, wsum, &total);
+            if (g < strips) {
+                const int64_t chunk = g >> 6;
+                const int lane = (int)(g & 63);
+                codes[(b * C + chunk) * 64 + lane] = (uint16_t)(carry + ex);
+                for (int i = 0; i < epl; ++i) {
+                    const uint32_t e = lb[g * epl + i];
+                    const uint32_t out = (enc == kEncSmall) ? (((e & 1u) << 15) | (e & 0xfffeu)) : e;
+                    entries[(((b * C + chunk) * H + (i >> 3)) * 64 + lane) * 8 + (i & 7)] =
+                        (uint16_t)out;
+                }
+            }
+            carry += total;
         }
-        __syncthreads();
+        if (threadIdx.x == 0 && (int64_t)carry != P) atomicOr(err_flag, 2);
     }
 }
 
@@ -278,14 +292,15 @@ hipError_t launch_stream_len(const uint32_t *off, int64_t nb, int64_t cols, int6
 }
 
 hipError_t launch_pack_stream(const uint16_t *pi, const uint32_t *off, int64_t nb, int64_t cols,
-                              int64_t P, int64_t S, int W, uint16_t *stream, uint32_t *hdr,
-                              int *err_flag) {
+                              int64_t P, int64_t C, int H, int enc, uint16_t *scratch,
+                              uint16_t *entries, uint16_t *codes, int *err_flag) {
+    const int64_t S = C * 64 * 8 * H;
     hipLaunchKernelGGL(k_pack_stream, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, pi, off, nb,
-                       (int)cols, P, S, stream);
+                       (int)cols, P, S, scratch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_stream_hdr, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, stream, nb,
-                       P, S, W, hdr, err_flag);
+    hipLaunchKernelGGL(k_finalize_stream, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, scratch,
+                       nb, P, C, H, enc, entries, codes, err_flag);
     return hipGetLastError();
 }
 
