@@ -111,7 +111,6 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
     {
         const int64_t longest = max_len[0] > max_len[1] ? max_len[0] : max_len[1];
         rsr::choose_launch_shape(longest, &h->H, &h->W);
-        if (h->W < rsr::min_waves_for_rows(h->k)) h->W = rsr::min_waves_for_rows(h->k);
         h->enc = (cols <= rsr::kSmallCols) ? rsr::kEncSmall : rsr::kEncBig;
         const int64_t chunk = (int64_t)rsr::kLoad * h->H;
         int64_t maxS = 0;
@@ -122,7 +121,17 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
             if (pd.C * chunk > maxS) maxS = pd.C * chunk;
         }
         const int64_t chunks[2] = {h->pass[0].C, h->pass[1].C};
-        rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
+        // fewer waves if the scatter phase's per-thread terms would not fit LDS
+        for (;;) {
+            rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
+            if (rsr::matvec_lds_bytes(P, cols, 4, h->k, h->fold.nact) <= rsr::kLdsBytes || h->W == 1)
+                break;
+            h->W -= 1;
+        }
+        if (rsr::matvec_lds_bytes(P, cols, 4, h->k, h->fold.nact) > rsr::kLdsBytes) {
+            rc = RSR_EUNSUPPORTED;
+            goto done;
+        }
         RSR_TRY(dev_alloc(&h->ftab, (size_t)h->fold.nrows * 16));
         RSR_TRY(rsr::launch_fold_tables(h->base, h->k, h->fold, h->ftab));
         RSR_TRY(dev_alloc(&scratch, (size_t)(nb * maxS)));
@@ -179,7 +188,7 @@ rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, 
         if (k > kmax) { free_handle(h); fail(RSR_EUNSUPPORTED); return nullptr; }
         h->P = ipow(h->base, k);
         h->nb = (rows + k - 1) / k;
-        if (rsr::matvec_lds_bytes(h->P, cols, 4) > rsr::kLdsBytes) {
+        if (rsr::matvec_lds_bytes(h->P, cols, 4, k, 1) > rsr::kLdsBytes) {  // even one fold wave
             free_handle(h);
             fail(RSR_EUNSUPPORTED);
             return nullptr;

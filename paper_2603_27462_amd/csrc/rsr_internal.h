@@ -13,7 +13,7 @@ constexpr int kLoad = 512;             // stream entries one 16-byte-per-lane wa
 constexpr int kMaxCols = 32766;        // index 'cols' is the zero slot and must fit 15 bits
 constexpr int kSmallCols = 16383;      // up to here an entry is tail<<15 | idx<<1
 constexpr int kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
-constexpr int kLdsMisc = 2048;         // wave-total terms and wave partials of the scatter phase
+constexpr int kLdsMisc = 1024;         // wave-total terms of the scatter phase
 
 // One pass of an RSR handle (binary, M+, M- or fused).
 //
@@ -96,8 +96,7 @@ const char *dense_matvec_kernel_name(int v_dtype);
 // waves per workgroup for blocks whose longest stream has `longest` entries.
 // The environment variables RSR_H and RSR_W override the choice (tuning only).
 void choose_launch_shape(int64_t longest, int *H, int *W);
-// The last step of the multiply kernel uses 16 threads per output row of a block.
-int min_waves_for_rows(int k);
+
 
 void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int npass,
                      FoldShape *fs);
@@ -105,10 +104,11 @@ hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int8_t *ftab
 hipError_t launch_wave_signs(int base, int k, const uint16_t *codes, int64_t nb, int64_t C, int W,
                              const FoldShape &fs, int pass, int8_t *wsign);
 
-// LDS bytes the RSR multiply kernel needs for a pass layout and vector type.
-inline int64_t matvec_lds_bytes(int64_t P, int64_t cols, int v_elem_bytes) {
-    int64_t vbytes = ((cols + 1) * v_elem_bytes + 15) / 16 * 16;
-    return P * 4 + kLdsMisc + vbytes;
+// LDS bytes the RSR multiply kernel needs: v and its zero slot, the wave-total terms,
+// E[P], and one term per output row and fold thread.
+inline int64_t matvec_lds_bytes(int64_t P, int64_t cols, int v_elem_bytes, int k, int nact) {
+    const int64_t vbytes = ((cols + 1) * v_elem_bytes + 15) / 16 * 16;
+    return vbytes + kLdsMisc + P * 4 + (int64_t)k * nact * 64 * 4;
 }
 
 }  // namespace rsr

@@ -48,7 +48,7 @@ struct PassArgs {
 struct FoldArgs {
     const int8_t *ftab;
     int ib[5];  // stage-1 share of part j: [ib[j], ib[j+1])
-    int k, m, Tc, Q, parts, nact, nrows;
+    int k, P, m, Tc, Q, parts, nact, nrows;
 };
 
 struct OutArgs {
@@ -221,16 +221,14 @@ __device__ __forceinline__ void lds_store_v(int byte_addr, VT x) {
 }
 
 // One pass (binary, M+, M- or fused) of one block.  FIRST: v still has to be staged into
-// LDS.  LAST: the output rows are written.
-template <typename VT, int H, int ENC, bool FIRST, bool LAST>
+// LDS and the output rows are overwritten; otherwise the pass adds to them.
+template <typename VT, int H, int ENC, bool FIRST>
 __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long long ldv, int n_in,
-                                         int W, const FoldArgs &f, const OutArgs &o,
-                                         float &final_r) {
+                                         int W, const FoldArgs &f, const OutArgs &o) {
     constexpr int PF = 4 / H;  // chunks requested together (16 dwords per lane)
-    // LDS (byte addresses): v (n_in + zero slot) | wave-total terms | wave partials | E[P]
+    // LDS (byte addresses): v (n_in + zero slot) | wave-total terms | E[P] | red[k][fold threads]
     const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
     const uint32_t corr_at = vbytes;          // float [16 waves][16 rows]
-    const uint32_t part_at = corr_at + 1024;  // float [16 waves][16 rows]
     const uint32_t e_at = vbytes + kLdsMisc;  // float [P]
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -373,26 +371,25 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
     RSR_STAMP(3);
 
     // ---- scatter: weighted sum over E ---------------------------------------
+    const int nfold = f.nact * 64;                     // threads of the fold waves
+    const uint32_t red_at = e_at + (uint32_t)f.P * 4u;  // float [k][nfold]
     if (w < f.nact) {  // only the waves that hold fold threads
-        float wt[16];
-        {
-            const uint32_t ww[4] = {wrow.x, wrow.y, wrow.z, wrow.w};
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                wt[r] = (float)(int)(signed char)((ww[r >> 2] >> (8 * (r & 3))) & 0xffu);
-        }
         float col = 0.0f;
         if (in_stage1) {
             // digits below m: the class c mod Tc decides the weight
             const int i0 = part == 0 ? f.ib[0] : part == 1 ? f.ib[1] : part == 2 ? f.ib[2] : f.ib[3];
             const int i1 = part == 0 ? f.ib[1] : part == 1 ? f.ib[2] : part == 2 ? f.ib[3] : f.ib[4];
-            const uint32_t at = e_at + (uint32_t)cls * 4u;
             const uint32_t step = (uint32_t)f.Tc * 4u;
+            uint32_t at = e_at + (uint32_t)cls * 4u + step * (uint32_t)i0;
+            const uint32_t last = e_at + (uint32_t)cls * 4u + step * (uint32_t)(i1 - 1);
             float c0s = 0.0f, c1s = 0.0f;
             for (int i = i0; i < i1; i += 8) {
                 float x[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = *lds_float(at + step * min(i + u, i1 - 1));
+                for (int u = 0; u < 8; ++u) {
+                    x[u] = *lds_float(min(at, last));  // reads past the share repeat its last entry
+                    at += step;
+                }
 #pragma unroll
                 for (int u = 0; u < 8; u += 2) {
                     if (i + u < i1) c0s += x[u];
@@ -404,46 +401,59 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
         // digits m..k-1 change only between c = Tc*i + Tc-1 and c+1
         float gq = 0.0f;
         if (tid < f.Q) gq = *lds_float(e_at + (uint32_t)(f.Tc * tid + f.Tc - 1) * 4u);
+        const uint32_t ww[4] = {wrow.x, wrow.y, wrow.z, wrow.w};
         float acc[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = wt[r] * (r < f.m ? col : gq);
+        for (int r = 0; r < 16; ++r) {
+            if (r < f.k) {
+                const float wt = (float)(int)(signed char)((ww[r >> 2] >> (8 * (r & 3))) & 0xffu);
+                acc[r] = wt * (r < f.m ? col : gq);
+            }
+        }
         for (int i = tid + nthreads; i < f.Q; i += nthreads) {  // only when Q > threads
             const uint4 xr = reinterpret_cast<const uint4 *>(f.ftab)[i];
             const uint32_t xw[4] = {xr.x, xr.y, xr.z, xr.w};
             const float gx = *lds_float(e_at + (uint32_t)(f.Tc * i + f.Tc - 1) * 4u);
 #pragma unroll
             for (int r = 0; r < 16; ++r)
-                if (r >= f.m)
+                if (r >= f.m && r < f.k)
                     acc[r] += (float)(int)(signed char)((xw[r >> 2] >> (8 * (r & 3))) & 0xffu) * gx;
         }
         RSR_STAMP(4);
-        // sum over the wave; lane 63 stores the wave's partial of every row
-        const uint32_t prow = part_at + (uint32_t)(w * 16) * 4u;
+        // every fold thread leaves its term of every row in LDS: red[r][tid]
+        uint32_t rp = red_at + (uint32_t)tid * 4u;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             if (r < f.k) {
-                const float x = wave_inclusive_scan(acc[r]);
-                if (lane == 63) *lds_float(prow + r * 4) = x;
+                *lds_float(rp) = acc[r];
+                rp += (uint32_t)nfold * 4u;
             }
         }
     }
     RSR_STAMP(5);
     __syncthreads();
     RSR_STAMP(6);
-    if (tid < 16 * f.k) {
-        // thread (row r, slot j): partial of wave j plus the wave-total term of wave j;
-        // the 16 slots of a row are one DPP row
-        const int r = tid >> 4, j = tid & 15;
-        float x = 0.0f;
-        if (j < f.nact) x = *lds_float(part_at + (j * 16 + r) * 4);
-        if (j < W) x += *lds_float(corr_at + (j * 16 + r) * 4);
-        x = row_inclusive_scan(x);
-        if (j == 15) {
-            final_r += a.sign * x;
-            if (LAST) {
+    // wave w sums rows w, w+W, ...: lane j takes red[r][j], red[r][j+64], ... and, for
+    // j < W, the wave-total term of wave j; one scan over the wave finishes the row
+#pragma unroll
+    for (int rr = 0; rr < 16; ++rr) {
+        const int r = w + rr * W;
+        if (r < f.k) {
+            const uint32_t at = red_at + (uint32_t)(r * nfold + lane) * 4u;
+            float x0 = 0.0f, x1 = 0.0f;
+            for (int i = 0; i < f.nact; i += 2) {
+                x0 += *lds_float(at + (uint32_t)i * 256u);
+                if (i + 1 < f.nact) x1 += *lds_float(at + (uint32_t)(i + 1) * 256u);
+            }
+            if (lane < W) x0 += *lds_float(corr_at + (lane * 16 + r) * 4);
+            const float tot = wave_inclusive_scan(x0 + x1);
+            if (lane == 63) {
                 const long long row = b * f.k + r;
-                if (row < o.n_out)
-                    o.out[(long long)blockIdx.y * o.ldo + row] = o.scale * final_r;
+                if (row < o.n_out) {
+                    float *dst = o.out + (long long)blockIdx.y * o.ldo + row;
+                    const float term = o.scale * a.sign * tot;
+                    *dst = FIRST ? term : *dst + term;  // pass 2 adds to what pass 1 wrote
+                }
             }
         }
     }
@@ -454,14 +464,11 @@ __global__ __launch_bounds__(1024) void k_rsr_matvec(const PassArgs a0, const vo
                                                      long long ldv, int n_in, int W,
                                                      const FoldArgs f, const PassArgs a1,
                                                      const OutArgs o) {
-    float final_r = 0.0f;  // thread 16*r + 15 accumulates output row b*k + r
     RSR_STAMP(0);
-    if (NPASS == 1) {
-        run_pass<VT, H, ENC, true, true>(a0, v, ldv, n_in, W, f, o, final_r);
-    } else {
-        run_pass<VT, H, ENC, true, false>(a0, v, ldv, n_in, W, f, o, final_r);
+    run_pass<VT, H, ENC, true>(a0, v, ldv, n_in, W, f, o);
+    if (NPASS == 2) {
         __syncthreads();
-        run_pass<VT, H, ENC, false, true>(a1, v, ldv, n_in, W, f, o, final_r);
+        run_pass<VT, H, ENC, false>(a1, v, ldv, n_in, W, f, o);
     }
     RSR_STAMP(7);
 }
@@ -556,19 +563,18 @@ __global__ void k_wave_signs(const uint16_t *__restrict__ codes, long long nb, i
 }  // namespace
 
 void choose_launch_shape(int64_t longest, int *H, int *W) {
+    // Two workgroups of up to 8 waves share a CU without register pressure; each wave
+    // should own at most two chunks, so the chunk grows with the stream (H = 1, 2, 4).
+    constexpr int kWaves = 8;
     int h = 4;
     for (int cand = 1; cand <= 4; cand *= 2)
-        if ((longest + kLoad * cand - 1) / (kLoad * cand) <= kMaxWaves) { h = cand; break; }
-    int64_t chunks = (longest + kLoad * h - 1) / (kLoad * h);
-    int w = (int)(chunks < 1 ? 1 : chunks > kMaxWaves ? kMaxWaves : chunks);
+        if ((longest + kLoad * cand - 1) / (kLoad * cand) <= 2 * kWaves) { h = cand; break; }
     if (const char *s = std::getenv("RSR_H")) {
         const int x = std::atoi(s);
-        if (x == 1 || x == 2 || x == 4) {
-            h = x;
-            chunks = (longest + kLoad * h - 1) / (kLoad * h);
-            w = (int)(chunks < 1 ? 1 : chunks > kMaxWaves ? kMaxWaves : chunks);
-        }
+        if (x == 1 || x == 2 || x == 4) h = x;
     }
+    const int64_t chunks = (longest + kLoad * h - 1) / (kLoad * h);
+    int w = (int)(chunks < 1 ? 1 : chunks > kWaves ? kWaves : chunks);
     if (const char *s = std::getenv("RSR_W")) {
         const int x = std::atoi(s);
         if (x >= 1 && x <= kMaxWaves) w = x;
@@ -576,8 +582,6 @@ void choose_launch_shape(int64_t longest, int *H, int *W) {
     *H = h;
     *W = w;
 }
-
-int min_waves_for_rows(int k) { return (16 * k + 63) / 64; }
 
 void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int npass,
                      FoldShape *fs) {
@@ -659,6 +663,7 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     x.f.ftab = h->ftab;
     for (int j = 0; j < 5; ++j) x.f.ib[j] = fs.ib[j];
     x.f.k = h->k;
+    x.f.P = (int)h->P;
     x.f.m = fs.m;
     x.f.Tc = fs.Tc;
     x.f.Q = fs.Q;
@@ -674,7 +679,7 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     if (const char *sp = std::getenv("RSR_STAMPS"))
         x.o.stamps = reinterpret_cast<long long *>(std::strtoull(sp, nullptr, 0));
 #endif
-    x.lds = (size_t)matvec_lds_bytes(h->P, h->cols, (v_dtype == RSR_BF16) ? 2 : 4);
+    x.lds = (size_t)matvec_lds_bytes(h->P, h->cols, (v_dtype == RSR_BF16) ? 2 : 4, h->k, fs.nact);
     x.stream = stream;
     return (v_dtype == RSR_BF16) ? launch_he<uint16_t>(x, h->H, h->enc)
                                  : launch_he<float>(x, h->H, h->enc);
