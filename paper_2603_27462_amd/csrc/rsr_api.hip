@@ -35,7 +35,8 @@ void free_handle(rsr_handle_s *h) {
         if (ps.codes) (void)hipFree(ps.codes);
         if (ps.wsign) (void)hipFree(ps.wsign);
     }
-    if (h->ftab) (void)hipFree(h->ftab);
+    if (h->fpack) (void)hipFree(h->fpack);
+    if (h->fshare) (void)hipFree(h->fshare);
     if (h->packed) (void)hipFree(h->packed);
     h->magic = 0;
     delete h;
@@ -121,19 +122,10 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
             if (pd.C * chunk > maxS) maxS = pd.C * chunk;
         }
         const int64_t chunks[2] = {h->pass[0].C, h->pass[1].C};
-        // fewer waves if the scatter phase's per-thread terms would not fit LDS
-        for (;;) {
-            rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
-            if (rsr::matvec_lds_bytes(P, cols, 4, h->k, h->fold.nact) <= rsr::kLdsBytes || h->W == 1)
-                break;
-            h->W -= 1;
-        }
-        if (rsr::matvec_lds_bytes(P, cols, 4, h->k, h->fold.nact) > rsr::kLdsBytes) {
-            rc = RSR_EUNSUPPORTED;
-            goto done;
-        }
-        RSR_TRY(dev_alloc(&h->ftab, (size_t)h->fold.nrows * 16));
-        RSR_TRY(rsr::launch_fold_tables(h->base, h->k, h->fold, h->ftab));
+        rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
+        RSR_TRY(dev_alloc(&h->fpack, (size_t)h->k * h->fold.G * 64));
+        RSR_TRY(dev_alloc(&h->fshare, (size_t)h->W * 64 * 2));
+        RSR_TRY(rsr::launch_fold_tables(h->base, h->k, h->fold, h->W, h->fpack, h->fshare));
         RSR_TRY(dev_alloc(&scratch, (size_t)(nb * maxS)));
         for (int ps = 0; ps < h->npass; ++ps) {
             rsr::PassData &pd = h->pass[ps];
@@ -188,7 +180,7 @@ rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, 
         if (k > kmax) { free_handle(h); fail(RSR_EUNSUPPORTED); return nullptr; }
         h->P = ipow(h->base, k);
         h->nb = (rows + k - 1) / k;
-        if (rsr::matvec_lds_bytes(h->P, cols, 4, k, 1) > rsr::kLdsBytes) {  // even one fold wave
+        if (rsr::matvec_lds_bytes(h->P, cols, 4, rsr::kMaxWaves) > rsr::kLdsBytes) {
             free_handle(h);
             fail(RSR_EUNSUPPORTED);
             return nullptr;
@@ -309,7 +301,7 @@ int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch) {
         for (int ps = 0; ps < h->npass; ++ps)
             weight_side += h->nb * (h->pass[ps].C * ((int64_t)rsr::kLoad * h->H * 2 + 64 * 2) +
                                     (int64_t)h->W * 16);
-        weight_side += (int64_t)h->fold.nrows * 16;
+        weight_side += (int64_t)h->k * h->fold.G * 256 + (int64_t)h->W * 64 * 8;
     }
     return weight_side + (int64_t)batch * (h->cols * vb + h->rows * 4);
 }
@@ -320,7 +312,7 @@ const char *rsr_kernel_name(rsr_handle_t h, int v_dtype) {
         return nullptr;
     }
     return h->kind == RSR_DENSE_TERNARY_P2 ? rsr::dense_matvec_kernel_name(v_dtype)
-                                           : rsr::rsr_matvec_kernel_name(v_dtype, h->H, h->enc, h->npass);
+                                           : rsr::rsr_matvec_kernel_name(v_dtype, h->H, h->enc, h->npass, rsr::matvec_is_single(h));
 }
 
 }  // extern "C"

@@ -1,0 +1,145 @@
+// Device-side building blocks of the RSR multiply kernels (gfx950, wave64): raw LDS
+// addressing, DPP scans, and the per-entry gather / tail-store steps written out
+// as instructions.  Included only by rsr_matvec.hip.
+#pragma once
+
+#include "rsr_internal.h"
+
+namespace rsr {
+namespace {
+
+typedef __attribute__((address_space(3))) float lds_f32;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4 lds_u128;
+
+__device__ __forceinline__ lds_f32 *lds_float(uint32_t addr) {
+    return reinterpret_cast<lds_f32 *>(static_cast<uintptr_t>(addr));
+}
+
+// ---- cross-lane primitives (DPP; wave64) -------------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float x) {
+    // x + (x moved by the DPP pattern); lanes without a source add 0
+    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+    return x + __int_as_float(moved);
+}
+
+// Inclusive prefix sum over each row of 16 lanes.
+__device__ __forceinline__ float row_inclusive_scan(float x) {
+    x = dpp_add<0x111, 0xf>(x);  // row_shr:1
+    x = dpp_add<0x112, 0xf>(x);  // row_shr:2
+    x = dpp_add<0x114, 0xf>(x);  // row_shr:4
+    x = dpp_add<0x118, 0xf>(x);  // row_shr:8
+    return x;
+}
+
+// Inclusive prefix sum over the 64 lanes, in lane order.
+__device__ __forceinline__ float wave_inclusive_scan(float x) {
+    x = row_inclusive_scan(x);
+    x = dpp_add<0x142, 0xa>(x);  // row_bcast:15 into rows 1 and 3
+    x = dpp_add<0x143, 0xc>(x);  // row_bcast:31 into rows 2 and 3
+    return x;
+}
+
+// Value of lane l-1 (0 in lane 0).
+__device__ __forceinline__ float wave_shift_right(float x) {
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x138 /* wave_shr:1 */, 0xf, 0xf, false));
+}
+
+__device__ __forceinline__ float lane63(float x) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
+
+// ---- the per-entry steps, written out as instructions --------------------------------
+// The compiler does not see the LDS operations below, so every consumer is tied
+// to them through register operands and the waits are explicit.
+
+// LDS byte address of the element of v an entry names.  HALF = 0: low 16 bits of d.
+template <typename VT, int ENC, int HALF>
+__device__ __forceinline__ uint32_t entry_addr(uint32_t d) {
+    constexpr bool wide = sizeof(VT) == 4;
+    if (ENC == kEncSmall) {  // tail<<15 | idx<<1
+        if (!wide) return HALF ? ((d >> 16) & 0x7ffeu) : (d & 0x7ffeu);
+        return HALF ? ((d >> 15) & 0xfffcu) : ((d & 0x7ffeu) << 1);
+    }
+    // idx<<1 | tail
+    if (!wide) return HALF ? ((d >> 16) & 0xfffeu) : (d & 0xfffeu);
+    return HALF ? ((d >> 15) & 0x1fffcu) : ((d & 0xfffeu) << 1);
+}
+
+// Gather one element of v as float bits.  For bf16 the 16 bits land in the high
+// half of g, whose low half is zero and stays zero (g is only ever written here).
+template <typename VT>
+__device__ __forceinline__ void gather(uint32_t &g, uint32_t addr) {
+    if (sizeof(VT) == 4)
+        asm volatile("ds_read_b32 %0, %1" : "=v"(g) : "v"(addr));
+    else
+        asm volatile("ds_read_u16_d16_hi %0, %1" : "+v"(g) : "v"(addr));
+}
+
+// Wait until at most N of the LDS operations issued so far are outstanding; the
+// eight registers are the results the caller is about to read.
+template <int N>
+__device__ __forceinline__ void lds_wait(uint32_t (&g)[8]) {
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]), "+v"(g[4]), "+v"(g[5]),
+                   "+v"(g[6]), "+v"(g[7])
+                 : "n"(N));
+}
+
+// If the entry is a tail: E[ptr] = base + s, ptr += 4.  Small encoding: the tail
+// flag is the sign of the 16-bit entry (low half: 16-bit compare on d; high
+// half: sign of the dword).
+template <int ENC, int HALF>
+__device__ __forceinline__ void tail_store(uint32_t d, float base, float s, uint32_t &ptr) {
+    float t;
+    uint64_t saved;
+    if (ENC == kEncSmall) {
+        if (HALF)
+            asm volatile(
+                "v_cmp_gt_i32 vcc, 0, %[d]\n\t"
+                "s_and_saveexec_b64 %[sv], vcc\n\t"
+                "v_add_f32 %[t], %[b], %[s]\n\t"
+                "ds_write_b32 %[p], %[t]\n\t"
+                "v_add_u32 %[p], 4, %[p]\n\t"
+                "s_mov_b64 exec, %[sv]"
+                : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
+                : [d] "v"(d), [b] "v"(base), [s] "v"(s)
+                : "vcc", "scc", "memory");
+        else
+            asm volatile(
+                "v_cmp_gt_i16 vcc, 0, %[d]\n\t"
+                "s_and_saveexec_b64 %[sv], vcc\n\t"
+                "v_add_f32 %[t], %[b], %[s]\n\t"
+                "ds_write_b32 %[p], %[t]\n\t"
+                "v_add_u32 %[p], 4, %[p]\n\t"
+                "s_mov_b64 exec, %[sv]"
+                : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
+                : [d] "v"(d), [b] "v"(base), [s] "v"(s)
+                : "vcc", "scc", "memory");
+    } else {
+        // idx<<1 | tail: bit 0 (low half) or bit 16 (high half)
+        asm volatile(
+            "v_bfe_i32 %[t], %[d], %[bit], 1\n\t"
+            "v_cmp_gt_i32 vcc, 0, %[t]\n\t"
+            "s_and_saveexec_b64 %[sv], vcc\n\t"
+            "v_add_f32 %[t], %[b], %[s]\n\t"
+            "ds_write_b32 %[p], %[t]\n\t"
+            "v_add_u32 %[p], 4, %[p]\n\t"
+            "s_mov_b64 exec, %[sv]"
+            : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
+            : [d] "v"(d), [b] "v"(base), [s] "v"(s), [bit] "n"(HALF ? 16 : 0)
+            : "vcc", "scc", "memory");
+    }
+}
+
+__device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+template <typename VT>
+__device__ __forceinline__ void lds_store_v(int byte_addr, VT x) {
+    *reinterpret_cast<__attribute__((address_space(3))) VT *>(static_cast<uintptr_t>(byte_addr)) = x;
+}
+
+}  // namespace
+}  // namespace rsr

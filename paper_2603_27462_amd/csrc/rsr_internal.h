@@ -36,10 +36,11 @@ struct PassData {
 // Launch-time constants of the scatter phase and the split of chunks over waves.
 struct FoldShape {
     int m = 0, Tc = 0, Q = 0;   // Tc = base^m classes handled by stage 1, Q = P / Tc
-    int parts = 1;              // threads sharing one class in stage 1 (1..4)
+    int parts = 1;              // threads sharing one class in level 1 (1 or 2)
     int ib[5] = {0, 0, 0, 0, 0};
     int nact = 0;               // waves that hold fold threads
-    int nrows = 0;              // rows of the weight table: max(Tc, Q)
+    int nrows = 0;              // entries per row of the weight table: max(Tc, Q)
+    int G = 0;                  // groups of 256 entries per row
     unsigned short cb[2][kMaxWaves + 1] = {};  // per pass: wave w owns chunks [cb[w], cb[w+1])
 };
 
@@ -54,7 +55,8 @@ struct rsr_handle_s {
     int64_t rows = 0, cols = 0, nb = 0, P = 0;
     rsr::PassData pass[2];
     rsr::FoldShape fold;
-    int8_t *ftab = nullptr;      // scatter weights [fold.nrows][16]
+    uint32_t *fpack = nullptr;   // scatter-phase weights, four per dword: [k][fold.G][64]
+    uint32_t *fshare = nullptr;  // level-1 share of every thread of the workgroup [W*64][2]
     uint8_t *packed = nullptr;   // dense kind: [rows][row_bytes], row_bytes % 16 == 0
     int64_t row_bytes = 0;
 };
@@ -89,7 +91,9 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
                              float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
 hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale,
                                float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
-const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass);
+const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass, bool single);
+// True when every pass has at most W chunks per block (one chunk per wave, no loops).
+bool matvec_is_single(const rsr_handle_s *h);
 const char *dense_matvec_kernel_name(int v_dtype);
 
 // Picks the chunk size (H loads of 512 entries per wave) and the number of
@@ -100,15 +104,16 @@ void choose_launch_shape(int64_t longest, int *H, int *W);
 
 void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int npass,
                      FoldShape *fs);
-hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int8_t *ftab);
+hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int W, uint32_t *fpack,
+                              uint32_t *fshare);
 hipError_t launch_wave_signs(int base, int k, const uint16_t *codes, int64_t nb, int64_t C, int W,
                              const FoldShape &fs, int pass, int8_t *wsign);
 
 // LDS bytes the RSR multiply kernel needs: v and its zero slot, the wave-total terms,
-// E[P], and one term per output row and fold thread.
-inline int64_t matvec_lds_bytes(int64_t P, int64_t cols, int v_elem_bytes, int k, int nact) {
+// E[P], and one level-1 sum per thread.
+inline int64_t matvec_lds_bytes(int64_t P, int64_t cols, int v_elem_bytes, int W) {
     const int64_t vbytes = ((cols + 1) * v_elem_bytes + 15) / 16 * 16;
-    return vbytes + kLdsMisc + P * 4 + (int64_t)k * nact * 64 * 4;
+    return vbytes + kLdsMisc + P * 4 + (int64_t)W * 64 * 4;
 }
 
 }  // namespace rsr

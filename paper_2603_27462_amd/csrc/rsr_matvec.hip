@@ -28,6 +28,7 @@
 #include <cstdio>
 #include <cstdlib>
 
+#include "rsr_device.h"
 #include "rsr_internal.h"
 
 namespace rsr {
@@ -46,9 +47,9 @@ struct PassArgs {
 };
 
 struct FoldArgs {
-    const int8_t *ftab;
-    int ib[5];  // stage-1 share of part j: [ib[j], ib[j+1])
-    int k, P, m, Tc, Q, parts, nact, nrows;
+    const uint32_t *fpack;
+    const uint2 *fshare;
+    int k, P, m, Tc, Q, G, parts;
 };
 
 struct OutArgs {
@@ -57,6 +58,7 @@ struct OutArgs {
     int n_out;
     float scale;
     long long *stamps;  // [blocks][8] shader-clock stamps of thread 0 (profiling builds only)
+    int stop_after;     // profiling builds only: leave the kernel after this phase (0 = never)
 };
 
 #ifdef RSR_PHASE_TIMING
@@ -68,134 +70,97 @@ struct OutArgs {
 #else
 #define RSR_STAMP(i) do { } while (0)
 #endif
+#ifdef RSR_PHASE_TIMING
+#define RSR_STOP(i) do { if (o.stop_after == (i)) return; } while (0)
+#else
+#define RSR_STOP(i) do { } while (0)
+#endif
 
-typedef __attribute__((address_space(3))) float lds_f32;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) u32x4 lds_u128;
+// ---- scatter phase: out[r] = sum_c E[c] (sgn_r(c) - sgn_r(c+1)) + wave-total terms -------
+// Level 1: thread (part, class t) adds up its share of E[t], E[t + Tc], E[t + 2 Tc], ...
+// (the entries that agree with t in the m lowest digits) and leaves the sum in
+// C1[part][t]; a class is shared by at most two threads.
+// Level 2: one wave per output row.  Rows r < m weigh the class sums with the weight of
+// (t, r); rows r >= m weigh E[Tc i + Tc - 1], the only entries where their digit
+// changes, with the weight of (i, r).  The wave-total terms join, one scan over the
+// wave adds everything up and lane 63 writes the row.
+// fpack[r][g][lane] packs, one byte each, the weights of j = lane + 64 (4g + u), u < 4:
+// r < m: sgn_r(j) - sgn_r((j+1) mod Tc); m <= r < k: sgn_{r-m}(j) - sgn_{r-m}(j+1).
+// share: x = first E index | number of entries << 16, y = class.
+struct ScatterArgs {
+    const uint32_t *fpack;
+    int k, m, Tc, Q, G, parts;  // G = groups of 256 table entries per row
+};
 
-__device__ __forceinline__ lds_f32 *lds_float(uint32_t addr) {
-    return reinterpret_cast<lds_f32 *>(static_cast<uintptr_t>(addr));
-}
-
-// ---- cross-lane primitives (DPP; wave64) -------------------------------------------
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_add(float x) {
-    // x + (x moved by the DPP pattern); lanes without a source add 0
-    const int moved = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
-    return x + __int_as_float(moved);
-}
-
-// Inclusive prefix sum over each row of 16 lanes.
-__device__ __forceinline__ float row_inclusive_scan(float x) {
-    x = dpp_add<0x111, 0xf>(x);  // row_shr:1
-    x = dpp_add<0x112, 0xf>(x);  // row_shr:2
-    x = dpp_add<0x114, 0xf>(x);  // row_shr:4
-    x = dpp_add<0x118, 0xf>(x);  // row_shr:8
-    return x;
-}
-
-// Inclusive prefix sum over the 64 lanes, in lane order.
-__device__ __forceinline__ float wave_inclusive_scan(float x) {
-    x = row_inclusive_scan(x);
-    x = dpp_add<0x142, 0xa>(x);  // row_bcast:15 into rows 1 and 3
-    x = dpp_add<0x143, 0xc>(x);  // row_bcast:31 into rows 2 and 3
-    return x;
-}
-
-// Value of lane l-1 (0 in lane 0).
-__device__ __forceinline__ float wave_shift_right(float x) {
-    return __int_as_float(
-        __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x138 /* wave_shr:1 */, 0xf, 0xf, false));
-}
-
-__device__ __forceinline__ float lane63(float x) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
-}
-
-// ---- the per-entry steps, written out as instructions --------------------------------
-// The compiler does not see the LDS operations below, so every consumer is tied
-// to them through register operands and the waits are explicit.
-
-// LDS byte address of the element of v an entry names.  HALF = 0: low 16 bits of d.
-template <typename VT, int ENC, int HALF>
-__device__ __forceinline__ uint32_t entry_addr(uint32_t d) {
-    constexpr bool wide = sizeof(VT) == 4;
-    if (ENC == kEncSmall) {  // tail<<15 | idx<<1
-        if (!wide) return HALF ? ((d >> 16) & 0x7ffeu) : (d & 0x7ffeu);
-        return HALF ? ((d >> 15) & 0xfffcu) : ((d & 0x7ffeu) << 1);
+template <bool FIRST>
+__device__ __forceinline__ void scatter_phase(const ScatterArgs &f, uint2 share2, uint32_t wpre,
+                                              uint32_t corr_at, uint32_t e_at, uint32_t c1_at,
+                                              int W, int w, int lane, int tid, float sign_scale,
+                                              float *out_rows, long long rows_left,
+                                              const OutArgs &o) {
+    const uint32_t share = share2.x;
+    const uint32_t cnt = share >> 16;
+    if (cnt) {
+        const uint32_t step = (uint32_t)f.Tc * 4u;
+        const uint32_t first = share & 0xffffu;
+        uint32_t at = e_at + first * 4u;
+        float c0s = 0.0f, c1s = 0.0f, c2s = 0.0f, c3s = 0.0f;
+        uint32_t i = 0;
+        for (; i + 4 <= cnt; i += 4) {
+            const float x0 = *lds_float(at);
+            const float x1 = *lds_float(at + step);
+            const float x2 = *lds_float(at + 2 * step);
+            const float x3 = *lds_float(at + 3 * step);
+            at += 4 * step;
+            c0s += x0; c1s += x1; c2s += x2; c3s += x3;
+        }
+        for (; i < cnt; ++i) {
+            c0s += *lds_float(at);
+            at += step;
+        }
+        const float col = (c0s + c1s) + (c2s + c3s);
+        *lds_float(c1_at + (uint32_t)tid * 4u) = col;  // C1[part][class]: tid = part * Tc + class
     }
-    // idx<<1 | tail
-    if (!wide) return HALF ? ((d >> 16) & 0xfffeu) : (d & 0xfffeu);
-    return HALF ? ((d >> 15) & 0x1fffcu) : ((d & 0xfffeu) << 1);
-}
-
-// Gather one element of v as float bits.  For bf16 the 16 bits land in the high
-// half of g, whose low half is zero and stays zero (g is only ever written here).
-template <typename VT>
-__device__ __forceinline__ void gather(uint32_t &g, uint32_t addr) {
-    if (sizeof(VT) == 4)
-        asm volatile("ds_read_b32 %0, %1" : "=v"(g) : "v"(addr));
-    else
-        asm volatile("ds_read_u16_d16_hi %0, %1" : "+v"(g) : "v"(addr));
-}
-
-// Wait until at most N of the LDS operations issued so far are outstanding; the
-// eight registers are the results the caller is about to read.
-template <int N>
-__device__ __forceinline__ void lds_wait(uint32_t (&g)[8]) {
-    asm volatile("s_waitcnt lgkmcnt(%8)"
-                 : "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]), "+v"(g[4]), "+v"(g[5]),
-                   "+v"(g[6]), "+v"(g[7])
-                 : "n"(N));
-}
-
-// If the entry is a tail: E[ptr] = base + s, ptr += 4.  Small encoding: the tail
-// flag is the sign of the 16-bit entry (low half: 16-bit compare on d; high
-// half: sign of the dword).
-template <int ENC, int HALF>
-__device__ __forceinline__ void tail_store(uint32_t d, float base, float s, uint32_t &ptr) {
-    float t;
-    uint64_t saved;
-    if (ENC == kEncSmall) {
-        if (HALF)
-            asm volatile(
-                "v_cmp_gt_i32 vcc, 0, %[d]\n\t"
-                "s_and_saveexec_b64 %[sv], vcc\n\t"
-                "v_add_f32 %[t], %[b], %[s]\n\t"
-                "ds_write_b32 %[p], %[t]\n\t"
-                "v_add_u32 %[p], 4, %[p]\n\t"
-                "s_mov_b64 exec, %[sv]"
-                : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
-                : [d] "v"(d), [b] "v"(base), [s] "v"(s)
-                : "vcc", "scc", "memory");
-        else
-            asm volatile(
-                "v_cmp_gt_i16 vcc, 0, %[d]\n\t"
-                "s_and_saveexec_b64 %[sv], vcc\n\t"
-                "v_add_f32 %[t], %[b], %[s]\n\t"
-                "ds_write_b32 %[p], %[t]\n\t"
-                "v_add_u32 %[p], 4, %[p]\n\t"
-                "s_mov_b64 exec, %[sv]"
-                : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
-                : [d] "v"(d), [b] "v"(base), [s] "v"(s)
-                : "vcc", "scc", "memory");
-    } else {
-        // idx<<1 | tail: bit 0 (low half) or bit 16 (high half)
-        asm volatile(
-            "v_bfe_i32 %[t], %[d], %[bit], 1\n\t"
-            "v_cmp_gt_i32 vcc, 0, %[t]\n\t"
-            "s_and_saveexec_b64 %[sv], vcc\n\t"
-            "v_add_f32 %[t], %[b], %[s]\n\t"
-            "ds_write_b32 %[p], %[t]\n\t"
-            "v_add_u32 %[p], 4, %[p]\n\t"
-            "s_mov_b64 exec, %[sv]"
-            : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
-            : [d] "v"(d), [b] "v"(base), [s] "v"(s), [bit] "n"(HALF ? 16 : 0)
-            : "vcc", "scc", "memory");
+    RSR_STAMP(5);
+    __syncthreads();
+    RSR_STAMP(6);
+    RSR_STOP(3);
+    for (int r = w; r < f.k; r += W) {
+        const bool low = r < f.m;
+        const int n = low ? f.Tc : f.Q;
+        // element j of the row: class sum C1[0][j] (+ C1[1][j]), or E[Tc j + Tc - 1]
+        const uint32_t base = low ? c1_at : e_at + (uint32_t)(f.Tc - 1) * 4u;
+        const uint32_t stride = low ? 4u : (uint32_t)f.Tc * 4u;
+        const bool two = low && f.parts == 2;
+        const uint32_t second = (uint32_t)f.Tc * 4u;
+        float x = 0.0f;
+        for (int g = 0; g * 256 < n; ++g) {
+            const uint32_t pk = (r == w && g == 0) ? wpre : f.fpack[(r * f.G + g) * 64 + lane];
+            const int j0 = lane + 256 * g;
+            // the four loads first, then the arithmetic (entries past n have weight 0)
+            const uint32_t a0 = base + stride * (uint32_t)min(j0, n - 1);
+            const uint32_t a1 = base + stride * (uint32_t)min(j0 + 64, n - 1);
+            const uint32_t a2 = base + stride * (uint32_t)min(j0 + 128, n - 1);
+            const uint32_t a3 = base + stride * (uint32_t)min(j0 + 192, n - 1);
+            float v0 = *lds_float(a0), v1 = *lds_float(a1), v2 = *lds_float(a2), v3 = *lds_float(a3);
+            if (two) {
+                const float u0 = *lds_float(a0 + second), u1 = *lds_float(a1 + second);
+                const float u2 = *lds_float(a2 + second), u3 = *lds_float(a3 + second);
+                v0 += u0; v1 += u1; v2 += u2; v3 += u3;
+            }
+            x += (float)(int)(signed char)(pk & 0xffu) * v0;
+            x += (float)(int)(signed char)((pk >> 8) & 0xffu) * v1;
+            x += (float)(int)(signed char)((pk >> 16) & 0xffu) * v2;
+            x += (float)(int)(signed char)(pk >> 24) * v3;
+        }
+        if (lane < W) x += *lds_float(corr_at + (lane * 16 + r) * 4);
+        const float tot = wave_inclusive_scan(x);
+        if (lane == 63 && r < rows_left) {
+            const float term = sign_scale * tot;
+            out_rows[r] = FIRST ? term : out_rows[r] + term;  // pass 2 adds to what pass 1 wrote
+        }
     }
 }
-
-__device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 // Requests chunks first..first+PF-1 of a wave (those below `end`): H 16-byte loads and
 // one start code per lane and chunk.  ep / cp already point at this lane.
@@ -213,11 +178,6 @@ __device__ __forceinline__ void load_group(const uint4 *ep, const uint16_t *cp, 
             code[f] = cp[(first + f) * 64];
         }
     }
-}
-
-template <typename VT>
-__device__ __forceinline__ void lds_store_v(int byte_addr, VT x) {
-    *reinterpret_cast<__attribute__((address_space(3))) VT *>(static_cast<uintptr_t>(byte_addr)) = x;
 }
 
 // One pass (binary, M+, M- or fused) of one block.  FIRST: v still has to be staged into
@@ -250,12 +210,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
     // requested now, used after the gather phase:
     // per (wave, row): sign of row r's digit in the first code closed by wave w+1
     const int8_t wsg8 = a.wsign[(b * W + w) * 16 + (lane & 15)];
-    // fold weights of this thread: one 16-byte row of the table
-    const int part = (tid >= f.Tc) + (tid >= 2 * f.Tc) + (tid >= 3 * f.Tc);
-    const int cls = tid - part * f.Tc;
-    const bool in_stage1 = part < f.parts;
-    const uint4 wrow =
-        reinterpret_cast<const uint4 *>(f.ftab)[min(in_stage1 ? cls : tid, f.nrows - 1)];
+    // scatter phase: this thread's level-1 share and the weights of the wave's first row
+    const ScatterArgs sa = {f.fpack, f.k, f.m, f.Tc, f.Q, f.G, f.parts};
+    const uint2 share = f.fshare[tid];
+    const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
     if (FIRST) {
         // stage v into LDS (16-byte copies when the source allows it); requested
         // before the stream so that it arrives first
@@ -370,93 +328,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
     __syncthreads();
     RSR_STAMP(3);
 
-    // ---- scatter: weighted sum over E ---------------------------------------
-    const int nfold = f.nact * 64;                     // threads of the fold waves
-    const uint32_t red_at = e_at + (uint32_t)f.P * 4u;  // float [k][nfold]
-    if (w < f.nact) {  // only the waves that hold fold threads
-        float col = 0.0f;
-        if (in_stage1) {
-            // digits below m: the class c mod Tc decides the weight
-            const int i0 = part == 0 ? f.ib[0] : part == 1 ? f.ib[1] : part == 2 ? f.ib[2] : f.ib[3];
-            const int i1 = part == 0 ? f.ib[1] : part == 1 ? f.ib[2] : part == 2 ? f.ib[3] : f.ib[4];
-            const uint32_t step = (uint32_t)f.Tc * 4u;
-            uint32_t at = e_at + (uint32_t)cls * 4u + step * (uint32_t)i0;
-            const uint32_t last = e_at + (uint32_t)cls * 4u + step * (uint32_t)(i1 - 1);
-            float c0s = 0.0f, c1s = 0.0f;
-            for (int i = i0; i < i1; i += 8) {
-                float x[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    x[u] = *lds_float(min(at, last));  // reads past the share repeat its last entry
-                    at += step;
-                }
-#pragma unroll
-                for (int u = 0; u < 8; u += 2) {
-                    if (i + u < i1) c0s += x[u];
-                    if (i + u + 1 < i1) c1s += x[u + 1];
-                }
-            }
-            col = c0s + c1s;
-        }
-        // digits m..k-1 change only between c = Tc*i + Tc-1 and c+1
-        float gq = 0.0f;
-        if (tid < f.Q) gq = *lds_float(e_at + (uint32_t)(f.Tc * tid + f.Tc - 1) * 4u);
-        const uint32_t ww[4] = {wrow.x, wrow.y, wrow.z, wrow.w};
-        float acc[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            if (r < f.k) {
-                const float wt = (float)(int)(signed char)((ww[r >> 2] >> (8 * (r & 3))) & 0xffu);
-                acc[r] = wt * (r < f.m ? col : gq);
-            }
-        }
-        for (int i = tid + nthreads; i < f.Q; i += nthreads) {  // only when Q > threads
-            const uint4 xr = reinterpret_cast<const uint4 *>(f.ftab)[i];
-            const uint32_t xw[4] = {xr.x, xr.y, xr.z, xr.w};
-            const float gx = *lds_float(e_at + (uint32_t)(f.Tc * i + f.Tc - 1) * 4u);
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (r >= f.m && r < f.k)
-                    acc[r] += (float)(int)(signed char)((xw[r >> 2] >> (8 * (r & 3))) & 0xffu) * gx;
-        }
-        RSR_STAMP(4);
-        // every fold thread leaves its term of every row in LDS: red[r][tid]
-        uint32_t rp = red_at + (uint32_t)tid * 4u;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            if (r < f.k) {
-                *lds_float(rp) = acc[r];
-                rp += (uint32_t)nfold * 4u;
-            }
-        }
-    }
-    RSR_STAMP(5);
-    __syncthreads();
-    RSR_STAMP(6);
-    // wave w sums rows w, w+W, ...: lane j takes red[r][j], red[r][j+64], ... and, for
-    // j < W, the wave-total term of wave j; one scan over the wave finishes the row
-#pragma unroll
-    for (int rr = 0; rr < 16; ++rr) {
-        const int r = w + rr * W;
-        if (r < f.k) {
-            const uint32_t at = red_at + (uint32_t)(r * nfold + lane) * 4u;
-            float x0 = 0.0f, x1 = 0.0f;
-            for (int i = 0; i < f.nact; i += 2) {
-                x0 += *lds_float(at + (uint32_t)i * 256u);
-                if (i + 1 < f.nact) x1 += *lds_float(at + (uint32_t)(i + 1) * 256u);
-            }
-            if (lane < W) x0 += *lds_float(corr_at + (lane * 16 + r) * 4);
-            const float tot = wave_inclusive_scan(x0 + x1);
-            if (lane == 63) {
-                const long long row = b * f.k + r;
-                if (row < o.n_out) {
-                    float *dst = o.out + (long long)blockIdx.y * o.ldo + row;
-                    const float term = o.scale * a.sign * tot;
-                    *dst = FIRST ? term : *dst + term;  // pass 2 adds to what pass 1 wrote
-                }
-            }
-        }
-    }
+    // ---- scatter ----------------------------------------------------------------
+    scatter_phase<FIRST>(sa, share, wpre, corr_at, e_at, e_at + (uint32_t)f.P * 4u, W, w, lane, tid,
+                         o.scale * a.sign, o.out + (long long)blockIdx.y * o.ldo + b * f.k,
+                         (long long)o.n_out - b * f.k, o);
 }
 
 template <typename VT, int H, int ENC, int NPASS>
@@ -473,6 +348,173 @@ __global__ __launch_bounds__(1024) void k_rsr_matvec(const PassArgs a0, const vo
     RSR_STAMP(7);
 }
 
+// ---- one chunk per wave ---------------------------------------------------------------
+// The common shape: the block's stream has at most W chunks, wave w owns chunk w, and
+// nothing loops.  Same phases as run_pass; the scatter phase takes its per-thread
+// constants (weights, first entry and count of the stage-1 share, stage-2 entry) from one
+// 32-byte record per fold thread.
+struct SecondPass {
+    const uint16_t *entries;
+    const uint16_t *codes;
+    const int8_t *wsign;
+    int C;
+    float sign;
+};
+
+template <typename VT, int H, int ENC, bool FIRST>
+__device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries,
+                                            const uint16_t *__restrict__ codes,
+                                            const int8_t *__restrict__ wsign, int C, float sign,
+                                            const void *__restrict__ v, long long ldv, int n_in,
+                                            int W, const FoldArgs &f, float *out, long long ldo,
+                                            int n_out, float scale, const OutArgs &o) {
+    const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
+    const uint32_t corr_at = vbytes;                    // float [16 waves][16 rows]
+    const uint32_t e_at = vbytes + kLdsMisc;            // float [P]
+    const uint32_t c1_at = e_at + (uint32_t)f.P * 4u;   // float [threads]: level-1 sums
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int nthreads = W * 64;
+    const long long b = blockIdx.x;
+    const ScatterArgs sa = {f.fpack, f.k, f.m, f.Tc, f.Q, f.G, f.parts};
+    const bool active = w < C;  // this wave owns a chunk
+
+    // ---- every global load of the pass is requested here ---------------------------------
+    const unsigned char *vg = reinterpret_cast<const unsigned char *>(v) +
+                              (long long)blockIdx.y * ldv * (long long)sizeof(VT);
+    const int nbytes = n_in * (int)sizeof(VT);
+    const int n16 = nbytes >> 4;
+    const bool v_aligned = (reinterpret_cast<uintptr_t>(vg) & 15) == 0;
+    const u32x4 *v16 = reinterpret_cast<const u32x4 *>(vg);
+    lds_u128 *l16 = reinterpret_cast<lds_u128 *>(static_cast<uintptr_t>(0));
+    u32x4 s0, s1, s2, s3;
+    const int j_0 = tid, j_1 = j_0 + nthreads, j_2 = j_1 + nthreads, j_3 = j_2 + nthreads;
+    if (FIRST && v_aligned && n16 > 0) {
+        // loads past the end are redirected to the last valid 16 bytes
+        s0 = v16[min(j_0, n16 - 1)];
+        s1 = v16[min(j_1, n16 - 1)];
+        s2 = v16[min(j_2, n16 - 1)];
+        s3 = v16[min(j_3, n16 - 1)];
+    }
+    uint4 q[H];
+    uint32_t code = 0;
+#pragma unroll
+    for (int h = 0; h < H; ++h) q[h] = make_uint4(0u, 0u, 0u, 0u);
+    if (active) {
+        const uint4 *ep = reinterpret_cast<const uint4 *>(entries) + ((b * C + w) * H) * 64 + lane;
+#pragma unroll
+        for (int h = 0; h < H; ++h) q[h] = ep[h * 64];
+        code = codes[(b * C + w) * 64 + lane];
+    }
+    const uint2 share = f.fshare[tid];
+    const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
+    const int8_t wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
+
+    // ---- stage v --------------------------------------------------------------------------
+    if (FIRST) {
+        if (v_aligned) {
+            if (n16 > 0) {
+                if (j_0 < n16) l16[j_0] = s0;
+                if (j_1 < n16) l16[j_1] = s1;
+                if (j_2 < n16) l16[j_2] = s2;
+                if (j_3 < n16) l16[j_3] = s3;
+                for (int j = j_3 + nthreads; j < n16; j += nthreads) l16[j] = v16[j];
+            }
+            for (int j = (n16 << 4) + tid * (int)sizeof(VT); j < nbytes;
+                 j += nthreads * (int)sizeof(VT))
+                lds_store_v<VT>(j, *reinterpret_cast<const VT *>(vg + j));
+        } else {
+            for (int j = tid * (int)sizeof(VT); j < nbytes; j += nthreads * (int)sizeof(VT))
+                lds_store_v<VT>(j, *reinterpret_cast<const VT *>(vg + j));
+        }
+        if (tid == 0) lds_store_v<VT>(nbytes, VT(0));
+    }
+    if (tid == 0) *lds_float(e_at) = 0.0f;
+    __syncthreads();
+    RSR_STAMP(1);
+    RSR_STOP(1);
+
+    // ---- gather + aggregate -------------------------------------------------------------
+    float total = 0.0f;
+    if (active) {
+        uint32_t d[H][4];
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            d[h][0] = q[h].x; d[h][1] = q[h].y; d[h][2] = q[h].z; d[h][3] = q[h].w;
+        }
+        uint32_t g[H][8];
+#pragma unroll
+        for (int h = 0; h < H; ++h)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) g[h][i] = 0u;
+        // gathers of 16-byte load h+1 are issued before those of load h are used
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            gather<VT>(g[0][2 * j], entry_addr<VT, ENC, 0>(d[0][j]));
+            gather<VT>(g[0][2 * j + 1], entry_addr<VT, ENC, 1>(d[0][j]));
+        }
+        float s[H][8];
+        float prev = 0.0f;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+            if (h + 1 < H) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    gather<VT>(g[h + 1][2 * j], entry_addr<VT, ENC, 0>(d[h + 1][j]));
+                    gather<VT>(g[h + 1][2 * j + 1], entry_addr<VT, ENC, 1>(d[h + 1][j]));
+                }
+                lds_wait<8>(g[h]);
+            } else {
+                lds_wait<0>(g[h]);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                prev += __uint_as_float(g[h][i]);
+                s[h][i] = prev;
+            }
+        }
+        const float incl = wave_inclusive_scan(prev);
+        const float base = wave_shift_right(incl);
+        uint32_t ptr = e_at + code * 4u;
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                tail_store<ENC, 0>(d[h][j], base, s[h][2 * j], ptr);
+                tail_store<ENC, 1>(d[h][j], base, s[h][2 * j + 1], ptr);
+            }
+        }
+        total = lane63(incl);
+    }
+    RSR_STAMP(2);
+    if (lane < 16) *lds_float(corr_at + (w * 16 + lane) * 4) = total * (float)wsg8;
+    lds_drain();
+    __syncthreads();
+    RSR_STAMP(3);
+    RSR_STOP(2);
+
+    // ---- scatter ----------------------------------------------------------------------
+    scatter_phase<FIRST>(sa, share, wpre, corr_at, e_at, c1_at, W, w, lane, tid, scale * sign,
+                         out + (long long)blockIdx.y * ldo + b * f.k, (long long)n_out - b * f.k, o);
+}
+
+template <typename VT, int H, int ENC, int NPASS>
+__global__ __launch_bounds__(1024) void k_rsr_matvec1(
+    const uint16_t *__restrict__ entries0, const uint16_t *__restrict__ codes0,
+    const void *__restrict__ v, int C0, int n_in, int W, long long ldv,
+    const int8_t *__restrict__ wsign0, const FoldArgs f, float sign0, const SecondPass a1,
+    const OutArgs o) {
+    RSR_STAMP(0);
+    single_pass<VT, H, ENC, true>(entries0, codes0, wsign0, C0, sign0, v, ldv, n_in, W, f, o.out,
+                                  o.ldo, o.n_out, o.scale, o);
+    if (NPASS == 2) {
+        __syncthreads();
+        single_pass<VT, H, ENC, false>(a1.entries, a1.codes, a1.wsign, a1.C, a1.sign, v, ldv, n_in, W,
+                                       f, o.out, o.ldo, o.n_out, o.scale, o);
+    }
+    RSR_STAMP(7);
+}
+
 struct LaunchArgs {
     PassArgs a0, a1;
     const void *v;
@@ -482,10 +524,34 @@ struct LaunchArgs {
     OutArgs o;
     size_t lds;
     hipStream_t stream;
+    bool single;  // every pass has at most W chunks: one chunk per wave, no loops
 };
 
 template <typename VT, int H, int ENC, int NPASS>
+hipError_t launch_single(const LaunchArgs &x) {
+    static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
+    auto kern = k_rsr_matvec1<VT, H, ENC, NPASS>;
+    if (x.lds > attr_bytes) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)x.lds);
+        if (e != hipSuccess) return e;
+        attr_bytes = x.lds;
+    }
+    SecondPass a1;
+    a1.entries = x.a1.entries;
+    a1.codes = x.a1.codes;
+    a1.wsign = x.a1.wsign;
+    a1.C = x.a1.C;
+    a1.sign = x.a1.sign;
+    hipLaunchKernelGGL(kern, dim3((unsigned)x.nblocks, (unsigned)x.batch), dim3(x.W * 64), x.lds,
+                       x.stream, x.a0.entries, x.a0.codes, x.v, x.a0.C, x.n_in, x.W, x.ldv,
+                       x.a0.wsign, x.f, x.a0.sign, a1, x.o);
+    return hipGetLastError();
+}
+
+template <typename VT, int H, int ENC, int NPASS>
 hipError_t launch(const LaunchArgs &x) {
+    if (x.single) return launch_single<VT, H, ENC, NPASS>(x);
     static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
     auto kern = k_rsr_matvec<VT, H, ENC, NPASS>;
     if (x.lds > attr_bytes) {
@@ -525,20 +591,40 @@ __device__ __forceinline__ int sgn_digit(uint32_t c, int r) {
     return d == 1u ? 1 : d == 2u ? -1 : 0;
 }
 
-// tab[t][r], r < m : sgn_r(t) - sgn_r((t+1) mod Tc) for t < Tc   (weight of class t)
-// tab[t][r], m <= r < k : sgn_{r-m}(t) - sgn_{r-m}(t+1) for t < Q  (weight of E[Tc*t + Tc-1])
+// fpack[r][g][lane], r < k: byte u holds the weight of j = lane + 64 (4g + u) in row r:
+// r < m: sgn_r(j) - sgn_r((j+1) mod Tc) for j < Tc (class j); m <= r < k:
+// sgn_{r-m}(j) - sgn_{r-m}(j+1) for j < Q (entry E[Tc*j + Tc-1]); 0 past the end.
+// fshare[t] for every thread t of the workgroup: x = first E index of its level-1 share
+// | number of entries << 16 (0 for threads without a share), y = its class.
 template <int BASE>
-__global__ void k_fold_table(int k, int m, int Tc, int Q, int nrows, int8_t *__restrict__ tab) {
+__global__ void k_fold_tables(int k, FoldShape fs, int threads, uint32_t *__restrict__ fpack,
+                              uint2 *__restrict__ fshare) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t >= nrows) return;
-    for (int r = 0; r < 16; ++r) {
-        int wgt = 0;
-        if (r < m) {
-            if (t < Tc) wgt = sgn_digit<BASE>(t, r) - sgn_digit<BASE>((t + 1 == Tc) ? 0 : t + 1, r);
-        } else if (r < k) {
-            if (t < Q) wgt = sgn_digit<BASE>(t, r - m) - sgn_digit<BASE>(t + 1, r - m);
+    if (t < k * fs.G * 64) {
+        const int lane = t & 63, g = (t >> 6) % fs.G, r = (t >> 6) / fs.G;
+        uint32_t pk = 0;
+        for (int u = 0; u < 4; ++u) {
+            const int j = lane + 64 * (4 * g + u);
+            int wgt = 0;
+            if (r < fs.m) {
+                if (j < fs.Tc)
+                    wgt = sgn_digit<BASE>(j, r) - sgn_digit<BASE>((j + 1 == fs.Tc) ? 0 : j + 1, r);
+            } else if (j < fs.Q) {
+                wgt = sgn_digit<BASE>(j, r - fs.m) - sgn_digit<BASE>(j + 1, r - fs.m);
+            }
+            pk |= ((uint32_t)wgt & 0xffu) << (8 * u);
         }
-        tab[t * 16 + r] = (int8_t)wgt;
+        fpack[t] = pk;
+    }
+    if (t < threads) {
+        uint2 share = make_uint2(0u, 0u);
+        if (t < fs.Tc * fs.parts) {
+            const int part = t / fs.Tc, cls = t - part * fs.Tc;
+            const int i0 = fs.ib[part], i1 = fs.ib[part + 1];
+            share.x = (uint32_t)(cls + fs.Tc * i0) | ((uint32_t)(i1 - i0) << 16);
+            share.y = (uint32_t)cls;
+        }
+        fshare[t] = share;
     }
 }
 
@@ -563,18 +649,19 @@ __global__ void k_wave_signs(const uint16_t *__restrict__ codes, long long nb, i
 }  // namespace
 
 void choose_launch_shape(int64_t longest, int *H, int *W) {
-    // Two workgroups of up to 8 waves share a CU without register pressure; each wave
-    // should own at most two chunks, so the chunk grows with the stream (H = 1, 2, 4).
+    // Preferred: one chunk per wave and at most 8 waves, so that two workgroups share a CU
+    // without register pressure; the chunk grows with the stream (H = 1, 2, 4).  Longer
+    // streams take up to 16 waves, and beyond that 8 waves that loop over their chunks.
     constexpr int kWaves = 8;
     int h = 4;
     for (int cand = 1; cand <= 4; cand *= 2)
-        if ((longest + kLoad * cand - 1) / (kLoad * cand) <= 2 * kWaves) { h = cand; break; }
+        if ((longest + kLoad * cand - 1) / (kLoad * cand) <= kWaves) { h = cand; break; }
     if (const char *s = std::getenv("RSR_H")) {
         const int x = std::atoi(s);
         if (x == 1 || x == 2 || x == 4) h = x;
     }
     const int64_t chunks = (longest + kLoad * h - 1) / (kLoad * h);
-    int w = (int)(chunks < 1 ? 1 : chunks > kWaves ? kWaves : chunks);
+    int w = (int)(chunks < 1 ? 1 : chunks <= kMaxWaves ? chunks : kWaves);
     if (const char *s = std::getenv("RSR_W")) {
         const int x = std::atoi(s);
         if (x >= 1 && x <= kMaxWaves) w = x;
@@ -595,7 +682,7 @@ void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int 
     int parts = 1;
     if (fs->Q <= fs->Tc) {
         parts = threads / fs->Tc;
-        if (parts > 4) parts = 4;
+        if (parts > 2) parts = 2;  // two additions into one class sum commute; three would not
         if (parts > fs->Q) parts = fs->Q;
         if (parts < 1) parts = 1;
     }
@@ -606,6 +693,7 @@ void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int 
     const int span2 = fs->Q < threads ? fs->Q : threads;
     fs->nact = ((span1 > span2 ? span1 : span2) + 63) / 64;
     fs->nrows = fs->Tc > fs->Q ? fs->Tc : fs->Q;
+    fs->G = (fs->nrows + 255) / 256;
     for (int ps = 0; ps < 2; ++ps)
         for (int w = 0; w <= kMaxWaves; ++w)
             fs->cb[ps][w] = (unsigned short)((ps < npass && w <= W)
@@ -613,15 +701,26 @@ void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int 
                                                  : 0);
 }
 
-hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int8_t *ftab) {
-    const int threads = 256, groups = (fs.nrows + threads - 1) / threads;
+hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int W, uint32_t *fpack,
+                              uint32_t *fshare_words) {
+    uint2 *fshare = reinterpret_cast<uint2 *>(fshare_words);
+    const int nthreads = W * 64;
+    const int rows = k * fs.G * 64;
+    const int span = rows > nthreads ? rows : nthreads;
+    const int threads = 256, groups = (span + threads - 1) / threads;
     if (base == 2)
-        hipLaunchKernelGGL(k_fold_table<2>, dim3(groups), dim3(threads), 0, 0, k, fs.m, fs.Tc, fs.Q,
-                           fs.nrows, ftab);
+        hipLaunchKernelGGL(k_fold_tables<2>, dim3(groups), dim3(threads), 0, 0, k, fs, nthreads, fpack,
+                           fshare);
     else
-        hipLaunchKernelGGL(k_fold_table<3>, dim3(groups), dim3(threads), 0, 0, k, fs.m, fs.Tc, fs.Q,
-                           fs.nrows, ftab);
+        hipLaunchKernelGGL(k_fold_tables<3>, dim3(groups), dim3(threads), 0, 0, k, fs, nthreads, fpack,
+                           fshare);
     return hipGetLastError();
+}
+
+bool matvec_is_single(const rsr_handle_s *h) {
+    for (int ps = 0; ps < h->npass; ++ps)
+        if (h->pass[ps].C > h->W) return false;
+    return true;
 }
 
 hipError_t launch_wave_signs(int base, int k, const uint16_t *codes, int64_t nb, int64_t C, int W,
@@ -660,39 +759,42 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     x.npass = h->npass;
     x.nblocks = (int)h->nb;
     x.batch = batch;
-    x.f.ftab = h->ftab;
-    for (int j = 0; j < 5; ++j) x.f.ib[j] = fs.ib[j];
+    x.f.fpack = h->fpack;
+    x.f.fshare = reinterpret_cast<const uint2 *>(h->fshare);
     x.f.k = h->k;
     x.f.P = (int)h->P;
     x.f.m = fs.m;
     x.f.Tc = fs.Tc;
     x.f.Q = fs.Q;
+    x.f.G = fs.G;
     x.f.parts = fs.parts;
-    x.f.nact = fs.nact;
-    x.f.nrows = fs.nrows;
     x.o.out = out;
     x.o.ldo = ldo;
     x.o.n_out = (int)h->rows;
     x.o.scale = scale;
     x.o.stamps = nullptr;
+    x.o.stop_after = 0;
 #ifdef RSR_PHASE_TIMING
+    if (const char *sp = std::getenv("RSR_STOP_AFTER")) x.o.stop_after = std::atoi(sp);
     if (const char *sp = std::getenv("RSR_STAMPS"))
         x.o.stamps = reinterpret_cast<long long *>(std::strtoull(sp, nullptr, 0));
 #endif
-    x.lds = (size_t)matvec_lds_bytes(h->P, h->cols, (v_dtype == RSR_BF16) ? 2 : 4, h->k, fs.nact);
+    x.lds = (size_t)matvec_lds_bytes(h->P, h->cols, (v_dtype == RSR_BF16) ? 2 : 4, h->W);
     x.stream = stream;
+    x.single = matvec_is_single(h);
     return (v_dtype == RSR_BF16) ? launch_he<uint16_t>(x, h->H, h->enc)
                                  : launch_he<float>(x, h->H, h->enc);
 }
 
-const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass) {
+const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass, bool single) {
     // one static string per instantiation, as a profiler prints the template arguments
-    static char names[2][3][2][2][48];
+    static char names[2][2][3][2][2][48];
     const int hi = (H == 1) ? 0 : (H == 2) ? 1 : 2;
-    char *n = names[v_dtype == RSR_BF16][hi][enc == kEncBig][npass == 2];
+    char *n = names[single][v_dtype == RSR_BF16][hi][enc == kEncBig][npass == 2];
     if (!n[0])
-        std::snprintf(n, sizeof(names[0][0][0][0]), "k_rsr_matvec<%s, %d, %d, %d>",
-                      v_dtype == RSR_BF16 ? "unsigned short" : "float", H, enc, npass);
+        std::snprintf(n, sizeof(names[0][0][0][0][0]), "k_rsr_matvec%s<%s, %d, %d, %d>",
+                      single ? "1" : "", v_dtype == RSR_BF16 ? "unsigned short" : "float", H, enc,
+                      npass);
     return n;
 }
 
