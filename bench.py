@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip warm and dense legs")
     ap.add_argument("--sets", type=int, default=0, help="weight sets to cycle (0 = from size)")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run one plain device copy of 256 MiB (a kernel of known traffic, "
+                         "to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -74,8 +77,8 @@ def time_graph(torch, launch_fn, steps, warmup):
 def main():
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (blocks shard without communication; "
-              "see DESIGN.md); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (blocks would shard across GPUs "
+              "without communication, but no such run exists); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -225,6 +228,12 @@ def main():
                       "1 thread) in %.1f s; oracle RSR matvec: %.2f matvec/s; host has %d cpus"
                       % (n, dt, n2 / dt2, os.cpu_count() or 0),
         }
+
+    if args.traffic_probe:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     print(json.dumps(result))
 

@@ -42,6 +42,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     path = path or _build.LIB_PATH
     if not os.path.exists(path):
         _build.build_library()
+    # PyTorch ships its own HIP runtime; it has to be in the process first so that
+    # librsr binds to the same one the tensors were allocated with.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(path)
     i64, vp, ci, cf = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     lib.rsr_preprocess.restype = vp
