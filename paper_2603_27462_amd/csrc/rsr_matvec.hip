@@ -125,6 +125,41 @@ __device__ __forceinline__ void scatter_phase(const ScatterArgs &f, uint2 share2
     __syncthreads();
     RSR_STAMP(6);
     RSR_STOP(3);
+    if (f.G == 1 && f.k <= W) {
+        // common shape: at most one row per wave, at most 256 table entries per row
+        if (w < f.k) {
+            const int r = w;
+            const bool low = r < f.m;
+            const int n = low ? f.Tc : f.Q;
+            const uint32_t base = low ? c1_at : e_at + (uint32_t)(f.Tc - 1) * 4u;
+            const uint32_t stride = low ? 4u : (uint32_t)f.Tc * 4u;
+            const uint32_t last = base + stride * (uint32_t)(n - 1);
+            const uint32_t a0 = min(base + stride * (uint32_t)lane, last);
+            const uint32_t a1 = min(a0 + 64 * stride, last);
+            const uint32_t a2 = min(a0 + 128 * stride, last);
+            const uint32_t a3 = min(a0 + 192 * stride, last);
+            float v0 = *lds_float(a0), v1 = *lds_float(a1), v2 = *lds_float(a2), v3 = *lds_float(a3);
+            float cr = 0.0f;
+            if (lane < W) cr = *lds_float(corr_at + (lane * 16 + r) * 4);
+            if (low && f.parts == 2) {
+                const uint32_t second = (uint32_t)f.Tc * 4u;
+                const float u0 = *lds_float(a0 + second), u1 = *lds_float(a1 + second);
+                const float u2 = *lds_float(a2 + second), u3 = *lds_float(a3 + second);
+                v0 += u0; v1 += u1; v2 += u2; v3 += u3;
+            }
+            // entries past n carry weight 0 in the table
+            float x = cr + (float)(int)(signed char)(wpre & 0xffu) * v0;
+            x += (float)(int)(signed char)((wpre >> 8) & 0xffu) * v1;
+            x += (float)(int)(signed char)((wpre >> 16) & 0xffu) * v2;
+            x += (float)(int)(signed char)(wpre >> 24) * v3;
+            const float tot = wave_inclusive_scan(x);
+            if (lane == 63 && r < rows_left) {
+                const float term = sign_scale * tot;
+                __builtin_nontemporal_store(FIRST ? term : out_rows[r] + term, &out_rows[r]);
+            }
+        }
+        return;
+    }
     for (int r = w; r < f.k; r += W) {
         const bool low = r < f.m;
         const int n = low ? f.Tc : f.Q;
@@ -157,7 +192,8 @@ __device__ __forceinline__ void scatter_phase(const ScatterArgs &f, uint2 share2
         const float tot = wave_inclusive_scan(x);
         if (lane == 63 && r < rows_left) {
             const float term = sign_scale * tot;
-            out_rows[r] = FIRST ? term : out_rows[r] + term;  // pass 2 adds to what pass 1 wrote
+            // pass 2 adds to what pass 1 wrote
+            __builtin_nontemporal_store(FIRST ? term : out_rows[r] + term, &out_rows[r]);
         }
     }
 }
@@ -401,10 +437,14 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
 #pragma unroll
     for (int h = 0; h < H; ++h) q[h] = make_uint4(0u, 0u, 0u, 0u);
     if (active) {
-        const uint4 *ep = reinterpret_cast<const uint4 *>(entries) + ((b * C + w) * H) * 64 + lane;
+        // the stream is read once: non-temporal loads keep it out of the way of v and the tables
+        const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + ((b * C + w) * H) * 64 + lane;
 #pragma unroll
-        for (int h = 0; h < H; ++h) q[h] = ep[h * 64];
-        code = codes[(b * C + w) * 64 + lane];
+        for (int h = 0; h < H; ++h) {
+            const u32x4 t = __builtin_nontemporal_load(&ep[h * 64]);
+            q[h] = make_uint4(t.x, t.y, t.z, t.w);
+        }
+        code = __builtin_nontemporal_load(&codes[(b * C + w) * 64 + lane]);
     }
     const uint2 share = f.fshare[tid];
     const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
