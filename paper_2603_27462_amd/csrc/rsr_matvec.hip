@@ -432,20 +432,18 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         s2 = v16[min(j_2, n16 - 1)];
         s3 = v16[min(j_3, n16 - 1)];
     }
+    // the stream is read once: non-temporal loads keep it out of the way of v and the tables.
+    // Waves without a chunk (w >= C) load the last chunk and ignore it: no branch, so
+    // nothing delays the requests.
     uint4 q[H];
-    uint32_t code = 0;
+    const int wc = min(w, C - 1);
+    const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + ((b * C + wc) * H) * 64 + lane;
 #pragma unroll
-    for (int h = 0; h < H; ++h) q[h] = make_uint4(0u, 0u, 0u, 0u);
-    if (active) {
-        // the stream is read once: non-temporal loads keep it out of the way of v and the tables
-        const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + ((b * C + w) * H) * 64 + lane;
-#pragma unroll
-        for (int h = 0; h < H; ++h) {
-            const u32x4 t = __builtin_nontemporal_load(&ep[h * 64]);
-            q[h] = make_uint4(t.x, t.y, t.z, t.w);
-        }
-        code = __builtin_nontemporal_load(&codes[(b * C + w) * 64 + lane]);
+    for (int h = 0; h < H; ++h) {
+        const u32x4 t = __builtin_nontemporal_load(&ep[h * 64]);
+        q[h] = make_uint4(t.x, t.y, t.z, t.w);
     }
+    uint32_t code = __builtin_nontemporal_load(&codes[(b * C + wc) * 64 + lane]);
     const uint2 share = f.fshare[tid];
     const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
     const int8_t wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
@@ -476,6 +474,7 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
 
     // ---- gather + aggregate -------------------------------------------------------------
     float total = 0.0f;
+    asm volatile("" : "+v"(code));  // first use of the stream: nothing above waits for it
     if (active) {
         uint32_t d[H][4];
 #pragma unroll
@@ -539,7 +538,7 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
 }
 
 template <typename VT, int H, int ENC, int NPASS>
-__global__ __launch_bounds__(1024) void k_rsr_matvec1(
+__global__ __launch_bounds__(1024, (H <= 2 ? 8 : 4)) void k_rsr_matvec1(
     const uint16_t *__restrict__ entries0, const uint16_t *__restrict__ codes0,
     const void *__restrict__ v, int C0, int n_in, int W, long long ldv,
     const int8_t *__restrict__ wsign0, const FoldArgs f, float sign0, const SecondPass a1,
