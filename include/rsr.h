@@ -59,7 +59,7 @@ enum {
  *         block is completed with zero rows, whose outputs are never written)
  *   cols  length of v, 1 <= cols <= 32766
  *   k     block height.  RSR_BINARY / RSR_TERNARY_2PASS: 1..15;
- *         RSR_TERNARY_FUSED: 1..10; in all cases 4*P + 4*(cols+1) + 5 KiB
+ *         RSR_TERNARY_FUSED: 1..10; in all cases 4*P + 4*(cols+1) + 9 KiB
  *         must fit the 160 KiB of LDS (P = 2^k or 3^k), else
  *         RSR_EUNSUPPORTED.  Ignored for RSR_DENSE_TERNARY_P2.
  *

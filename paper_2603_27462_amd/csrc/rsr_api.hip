@@ -124,7 +124,7 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
         const int64_t chunks[2] = {h->pass[0].C, h->pass[1].C};
         rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
         RSR_TRY(dev_alloc(&h->fpack, (size_t)h->k * h->fold.G * 64));
-        RSR_TRY(dev_alloc(&h->fshare, (size_t)h->W * 64 * 2));
+        RSR_TRY(dev_alloc(&h->fshare, (size_t)h->W * 64));
         RSR_TRY(rsr::launch_fold_tables(h->base, h->k, h->fold, h->W, h->fpack, h->fshare));
         RSR_TRY(dev_alloc(&scratch, (size_t)(nb * maxS)));
         for (int ps = 0; ps < h->npass; ++ps) {

@@ -37,7 +37,7 @@ struct PassData {
 struct FoldShape {
     int m = 0, Tc = 0, Q = 0;   // Tc = base^m classes handled by stage 1, Q = P / Tc
     int parts = 1;              // threads sharing one class in level 1 (1 or 2)
-    int ib[5] = {0, 0, 0, 0, 0};
+    int cnt1 = 0;               // entries every level-1 thread adds: ceil(Q / parts)
     int nact = 0;               // waves that hold fold threads
     int nrows = 0;              // entries per row of the weight table: max(Tc, Q)
     int G = 0;                  // groups of 256 entries per row
@@ -56,7 +56,7 @@ struct rsr_handle_s {
     rsr::PassData pass[2];
     rsr::FoldShape fold;
     uint32_t *fpack = nullptr;   // scatter-phase weights, four per dword: [k][fold.G][64]
-    uint32_t *fshare = nullptr;  // level-1 share of every thread of the workgroup [W*64][2]
+    uint32_t *fshare = nullptr;  // first entry of the level-1 share of every thread [W*64]
     uint8_t *packed = nullptr;   // dense kind: [rows][row_bytes], row_bytes % 16 == 0
     int64_t row_bytes = 0;
 };
@@ -110,10 +110,10 @@ hipError_t launch_wave_signs(int base, int k, const uint16_t *codes, int64_t nb,
                              const FoldShape &fs, int pass, int8_t *wsign);
 
 // LDS bytes the RSR multiply kernel needs: v and its zero slot, the wave-total terms,
-// E[P], and one level-1 sum per thread.
+// E[P] followed by a row of zeros (at most one per thread), and one level-1 sum per thread.
 inline int64_t matvec_lds_bytes(int64_t P, int64_t cols, int v_elem_bytes, int W) {
     const int64_t vbytes = ((cols + 1) * v_elem_bytes + 15) / 16 * 16;
-    return vbytes + kLdsMisc + P * 4 + (int64_t)W * 64 * 4;
+    return vbytes + kLdsMisc + P * 4 + 2 * (int64_t)W * 64 * 4;
 }
 
 }  // namespace rsr

@@ -48,8 +48,8 @@ struct PassArgs {
 
 struct FoldArgs {
     const uint32_t *fpack;
-    const uint2 *fshare;
-    int k, P, m, Tc, Q, G, parts;
+    const uint32_t *fshare;
+    int k, P, m, Tc, Q, G, parts, cnt1;
 };
 
 struct OutArgs {
@@ -79,47 +79,117 @@ struct OutArgs {
 // ---- scatter phase: out[r] = sum_c E[c] (sgn_r(c) - sgn_r(c+1)) + wave-total terms -------
 // Level 1: thread (part, class t) adds up its share of E[t], E[t + Tc], E[t + 2 Tc], ...
 // (the entries that agree with t in the m lowest digits) and leaves the sum in
-// C1[part][t]; a class is shared by at most two threads.
+// C1[part][t]; a class is shared by at most two threads.  Every thread adds the same
+// number of entries (cnt1): E is followed by one row of Tc zeros, which the second part
+// reads when Q is odd.
 // Level 2: one wave per output row.  Rows r < m weigh the class sums with the weight of
 // (t, r); rows r >= m weigh E[Tc i + Tc - 1], the only entries where their digit
 // changes, with the weight of (i, r).  The wave-total terms join, one scan over the
 // wave adds everything up and lane 63 writes the row.
 // fpack[r][g][lane] packs, one byte each, the weights of j = lane + 64 (4g + u), u < 4:
 // r < m: sgn_r(j) - sgn_r((j+1) mod Tc); m <= r < k: sgn_{r-m}(j) - sgn_{r-m}(j+1).
-// share: x = first E index | number of entries << 16, y = class.
+// share: x = first E index of the thread's level-1 share (0xffffffff: no share).
+//
+// A wave64 vector instruction occupies its SIMD for four cycles, and with four waves per
+// SIMD the vector instruction count is what the phases after the first barrier cost.
+// Everything below that does not depend on E -- LDS addresses, unpacked weights,
+// predicates -- is therefore computed by prepare_scatter() while the global loads of
+// the pass are still in flight, and pinned in registers until it is used.
 struct ScatterArgs {
     const uint32_t *fpack;
-    int k, m, Tc, Q, G, parts;  // G = groups of 256 table entries per row
+    int k, m, Tc, Q, G, parts, cnt1;  // G = groups of 256 table entries per row
 };
 
+constexpr int kL1Regs = 16;  // level-1 entries per thread covered by prepared addresses
+
+struct ScatterPrep {
+    uint32_t a1[kL1Regs];  // level 1: LDS addresses of the thread's first entries
+    uint32_t c1_store;     // level 1: where the thread's sum goes
+    uint32_t la[8];        // level 2 (one row per wave): class sums / entries of the row
+    uint32_t corr_a;       // level 2: wave-total term of lane's wave for this row
+    float wf[4];           // level 2: weights of the four elements
+    bool has_share;
+};
+
+template <typename T>
+__device__ __forceinline__ void pin(T &x) {
+    asm volatile("" : "+v"(x));
+}
+
+__device__ __forceinline__ void prepare_scatter(ScatterPrep &sp, const ScatterArgs &f,
+                                                uint2 share2, uint32_t wpre, uint32_t corr_at,
+                                                uint32_t e_at, uint32_t c1_at, int W, int w,
+                                                int lane, int tid) {
+    const uint32_t step = (uint32_t)f.Tc * 4u;
+    sp.has_share = share2.x != 0xffffffffu;
+    const uint32_t first = e_at + (sp.has_share ? share2.x : 0u) * 4u;
+#pragma unroll
+    for (int i = 0; i < kL1Regs; ++i) {
+        // entries past the share read E[0], which is zero
+        sp.a1[i] = (i < f.cnt1) ? first + (uint32_t)i * step : e_at;
+        pin(sp.a1[i]);
+    }
+    sp.c1_store = c1_at + (uint32_t)tid * 4u;  // C1[part][class]: tid = part * Tc + class
+    pin(sp.c1_store);
+    // level 2, one row per wave (used when G == 1 and k <= W)
+    const int r = min(w, f.k - 1);
+    const bool low = r < f.m;
+    const int n = low ? f.Tc : f.Q;
+    const uint32_t base = low ? c1_at : e_at + (uint32_t)(f.Tc - 1) * 4u;
+    const uint32_t stride = low ? 4u : step;
+    const uint32_t last = base + stride * (uint32_t)(n - 1);
+    sp.la[0] = min(base + stride * (uint32_t)lane, last);
+    sp.la[1] = min(sp.la[0] + 64 * stride, last);
+    sp.la[2] = min(sp.la[0] + 128 * stride, last);
+    sp.la[3] = min(sp.la[0] + 192 * stride, last);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        sp.la[4 + j] = sp.la[j] + step;  // the second part's class sums
+        pin(sp.la[j]);
+        pin(sp.la[4 + j]);
+    }
+    sp.corr_a = (lane < W) ? corr_at + (uint32_t)(lane * 16 + r) * 4u : e_at;
+    pin(sp.corr_a);
+    sp.wf[0] = (float)(int)(signed char)(wpre & 0xffu);
+    sp.wf[1] = (float)(int)(signed char)((wpre >> 8) & 0xffu);
+    sp.wf[2] = (float)(int)(signed char)((wpre >> 16) & 0xffu);
+    sp.wf[3] = (float)(int)(signed char)(wpre >> 24);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) pin(sp.wf[j]);
+}
+
 template <bool FIRST>
-__device__ __forceinline__ void scatter_phase(const ScatterArgs &f, uint2 share2, uint32_t wpre,
-                                              uint32_t corr_at, uint32_t e_at, uint32_t c1_at,
-                                              int W, int w, int lane, int tid, float sign_scale,
-                                              float *out_rows, long long rows_left,
-                                              const OutArgs &o) {
-    const uint32_t share = share2.x;
-    const uint32_t cnt = share >> 16;
-    if (cnt) {
-        const uint32_t step = (uint32_t)f.Tc * 4u;
-        const uint32_t first = share & 0xffffu;
-        uint32_t at = e_at + first * 4u;
-        float c0s = 0.0f, c1s = 0.0f, c2s = 0.0f, c3s = 0.0f;
-        uint32_t i = 0;
-        for (; i + 4 <= cnt; i += 4) {
-            const float x0 = *lds_float(at);
-            const float x1 = *lds_float(at + step);
-            const float x2 = *lds_float(at + 2 * step);
-            const float x3 = *lds_float(at + 3 * step);
-            at += 4 * step;
-            c0s += x0; c1s += x1; c2s += x2; c3s += x3;
+__device__ __forceinline__ void scatter_phase(const ScatterArgs &f, const ScatterPrep &sp,
+                                              uint32_t wpre, uint32_t corr_at, uint32_t e_at,
+                                              uint32_t c1_at, int W, int w, int lane, int tid,
+                                              float sign_scale, float *out_rows,
+                                              long long rows_left, const OutArgs &o) {
+    if (sp.has_share) {
+        float col;
+        if (f.cnt1 <= 4) {
+            const float x0 = *lds_float(sp.a1[0]), x1 = *lds_float(sp.a1[1]);
+            const float x2 = *lds_float(sp.a1[2]), x3 = *lds_float(sp.a1[3]);
+            col = (x0 + x1) + (x2 + x3);
+        } else {
+            float x[kL1Regs];
+#pragma unroll
+            for (int i = 0; i < kL1Regs; ++i) x[i] = *lds_float(sp.a1[i]);
+            float rest = 0.0f;
+            if (f.cnt1 > kL1Regs) {
+                const uint32_t step = (uint32_t)f.Tc * 4u;
+                uint32_t at = sp.a1[kL1Regs - 1] + step;
+                for (int i = kL1Regs; i < f.cnt1; ++i) {
+                    rest += *lds_float(at);
+                    at += step;
+                }
+            }
+#pragma unroll
+            for (int d = 1; d < kL1Regs; d *= 2)
+#pragma unroll
+                for (int i = 0; i + d < kL1Regs; i += 2 * d) x[i] += x[i + d];
+            col = x[0] + rest;
         }
-        for (; i < cnt; ++i) {
-            c0s += *lds_float(at);
-            at += step;
-        }
-        const float col = (c0s + c1s) + (c2s + c3s);
-        *lds_float(c1_at + (uint32_t)tid * 4u) = col;  // C1[part][class]: tid = part * Tc + class
+        *lds_float(sp.c1_store) = col;
     }
     RSR_STAMP(5);
     __syncthreads();
@@ -129,29 +199,19 @@ __device__ __forceinline__ void scatter_phase(const ScatterArgs &f, uint2 share2
         // common shape: at most one row per wave, at most 256 table entries per row
         if (w < f.k) {
             const int r = w;
-            const bool low = r < f.m;
-            const int n = low ? f.Tc : f.Q;
-            const uint32_t base = low ? c1_at : e_at + (uint32_t)(f.Tc - 1) * 4u;
-            const uint32_t stride = low ? 4u : (uint32_t)f.Tc * 4u;
-            const uint32_t last = base + stride * (uint32_t)(n - 1);
-            const uint32_t a0 = min(base + stride * (uint32_t)lane, last);
-            const uint32_t a1 = min(a0 + 64 * stride, last);
-            const uint32_t a2 = min(a0 + 128 * stride, last);
-            const uint32_t a3 = min(a0 + 192 * stride, last);
-            float v0 = *lds_float(a0), v1 = *lds_float(a1), v2 = *lds_float(a2), v3 = *lds_float(a3);
-            float cr = 0.0f;
-            if (lane < W) cr = *lds_float(corr_at + (lane * 16 + r) * 4);
-            if (low && f.parts == 2) {
-                const uint32_t second = (uint32_t)f.Tc * 4u;
-                const float u0 = *lds_float(a0 + second), u1 = *lds_float(a1 + second);
-                const float u2 = *lds_float(a2 + second), u3 = *lds_float(a3 + second);
+            float v0 = *lds_float(sp.la[0]), v1 = *lds_float(sp.la[1]);
+            float v2 = *lds_float(sp.la[2]), v3 = *lds_float(sp.la[3]);
+            const float cr = *lds_float(sp.corr_a);
+            if (r < f.m && f.parts == 2) {
+                const float u0 = *lds_float(sp.la[4]), u1 = *lds_float(sp.la[5]);
+                const float u2 = *lds_float(sp.la[6]), u3 = *lds_float(sp.la[7]);
                 v0 += u0; v1 += u1; v2 += u2; v3 += u3;
             }
-            // entries past n carry weight 0 in the table
-            float x = cr + (float)(int)(signed char)(wpre & 0xffu) * v0;
-            x += (float)(int)(signed char)((wpre >> 8) & 0xffu) * v1;
-            x += (float)(int)(signed char)((wpre >> 16) & 0xffu) * v2;
-            x += (float)(int)(signed char)(wpre >> 24) * v3;
+            // entries past the end of the row carry weight 0 in the table
+            float x = cr + sp.wf[0] * v0;
+            x += sp.wf[1] * v1;
+            x += sp.wf[2] * v2;
+            x += sp.wf[3] * v3;
             const float tot = wave_inclusive_scan(x);
             if (lane == 63 && r < rows_left) {
                 const float term = sign_scale * tot;
@@ -247,9 +307,11 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
     // per (wave, row): sign of row r's digit in the first code closed by wave w+1
     const int8_t wsg8 = a.wsign[(b * W + w) * 16 + (lane & 15)];
     // scatter phase: this thread's level-1 share and the weights of the wave's first row
-    const ScatterArgs sa = {f.fpack, f.k, f.m, f.Tc, f.Q, f.G, f.parts};
-    const uint2 share = f.fshare[tid];
+    const ScatterArgs sa = {f.fpack, f.k, f.m, f.Tc, f.Q, f.G, f.parts, f.cnt1};
+    const uint2 share = make_uint2(f.fshare[tid], 0u);
     const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
+    const uint32_t z_at = e_at + (uint32_t)f.P * 4u;    // float [Tc]: zeros behind E
+    const uint32_t c1_at = z_at + (uint32_t)f.Tc * 4u;  // float [threads]: level-1 sums
     if (FIRST) {
         // stage v into LDS (16-byte copies when the source allows it); requested
         // before the stream so that it arrives first
@@ -288,6 +350,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
         load_group<H, PF>(ep, cp, c0, c1, q, code);
     }
     if (tid == 0) *lds_float(e_at) = 0.0f;
+    if (tid < f.Tc) *lds_float(z_at + (uint32_t)tid * 4u) = 0.0f;
     __syncthreads();
     RSR_STAMP(1);
 
@@ -360,12 +423,15 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
     }
     RSR_STAMP(2);
     if (lane < 16) *lds_float(corr_at + (w * 16 + lane) * 4) = run * (float)wsg8;
+    // (this kernel keeps its registers for the chunk loop: the scatter constants are made here)
+    ScatterPrep sp;
+    prepare_scatter(sp, sa, share, wpre, corr_at, e_at, c1_at, W, w, lane, tid);
     lds_drain();
     __syncthreads();
     RSR_STAMP(3);
 
     // ---- scatter ----------------------------------------------------------------
-    scatter_phase<FIRST>(sa, share, wpre, corr_at, e_at, e_at + (uint32_t)f.P * 4u, W, w, lane, tid,
+    scatter_phase<FIRST>(sa, sp, wpre, corr_at, e_at, c1_at, W, w, lane, tid,
                          o.scale * a.sign, o.out + (long long)blockIdx.y * o.ldo + b * f.k,
                          (long long)o.n_out - b * f.k, o);
 }
@@ -407,15 +473,21 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
     const uint32_t corr_at = vbytes;                    // float [16 waves][16 rows]
     const uint32_t e_at = vbytes + kLdsMisc;            // float [P]
-    const uint32_t c1_at = e_at + (uint32_t)f.P * 4u;   // float [threads]: level-1 sums
+    const uint32_t z_at = e_at + (uint32_t)f.P * 4u;    // float [Tc]: zeros behind E
+    const uint32_t c1_at = z_at + (uint32_t)f.Tc * 4u;  // float [threads]: level-1 sums
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = W * 64;
     const long long b = blockIdx.x;
-    const ScatterArgs sa = {f.fpack, f.k, f.m, f.Tc, f.Q, f.G, f.parts};
+    const ScatterArgs sa = {f.fpack, f.k, f.m, f.Tc, f.Q, f.G, f.parts, f.cnt1};
     const bool active = w < C;  // this wave owns a chunk
 
-    // ---- every global load of the pass is requested here ---------------------------------
+    // ---- every global load of the pass is requested here: the small tables first (they
+    // are turned into scatter-phase constants while the rest is in flight), then v, then
+    // the stream ------------------------------------------------------------------------------
+    const uint2 share = make_uint2(f.fshare[tid], 0u);
+    const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
+    const int8_t wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
     const unsigned char *vg = reinterpret_cast<const unsigned char *>(v) +
                               (long long)blockIdx.y * ldv * (long long)sizeof(VT);
     const int nbytes = n_in * (int)sizeof(VT);
@@ -444,9 +516,21 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         q[h] = make_uint4(t.x, t.y, t.z, t.w);
     }
     uint32_t code = __builtin_nontemporal_load(&codes[(b * C + wc) * 64 + lane]);
-    const uint2 share = f.fshare[tid];
-    const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
-    const int8_t wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
+
+    // ---- work that needs no stream data, done while the loads are in flight ----------------
+    ScatterPrep sp;
+    prepare_scatter(sp, sa, share, wpre, corr_at, e_at, c1_at, W, w, lane, tid);
+    float wsg = (float)wsg8;
+    pin(wsg);
+    uint32_t g[H][8];  // gather targets: for bf16 the low halves must be zero
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            g[h][i] = 0u;
+            pin(g[h][i]);
+        }
+    if (tid < f.Tc) *lds_float(z_at + (uint32_t)tid * 4u) = 0.0f;
 
     // ---- stage v --------------------------------------------------------------------------
     if (FIRST) {
@@ -481,11 +565,6 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         for (int h = 0; h < H; ++h) {
             d[h][0] = q[h].x; d[h][1] = q[h].y; d[h][2] = q[h].z; d[h][3] = q[h].w;
         }
-        uint32_t g[H][8];
-#pragma unroll
-        for (int h = 0; h < H; ++h)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) g[h][i] = 0u;
         // gathers of 16-byte load h+1 are issued before those of load h are used
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
@@ -508,7 +587,7 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                prev += __uint_as_float(g[h][i]);
+                prev = (h == 0 && i == 0) ? __uint_as_float(g[0][0]) : prev + __uint_as_float(g[h][i]);
                 s[h][i] = prev;
             }
         }
@@ -526,19 +605,19 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         total = lane63(incl);
     }
     RSR_STAMP(2);
-    if (lane < 16) *lds_float(corr_at + (w * 16 + lane) * 4) = total * (float)wsg8;
+    if (lane < 16) *lds_float(corr_at + (w * 16 + lane) * 4) = total * wsg;
     lds_drain();
     __syncthreads();
     RSR_STAMP(3);
     RSR_STOP(2);
 
     // ---- scatter ----------------------------------------------------------------------
-    scatter_phase<FIRST>(sa, share, wpre, corr_at, e_at, c1_at, W, w, lane, tid, scale * sign,
+    scatter_phase<FIRST>(sa, sp, wpre, corr_at, e_at, c1_at, W, w, lane, tid, scale * sign,
                          out + (long long)blockIdx.y * ldo + b * f.k, (long long)n_out - b * f.k, o);
 }
 
 template <typename VT, int H, int ENC, int NPASS>
-__global__ __launch_bounds__(1024, (H <= 2 ? 8 : 4)) void k_rsr_matvec1(
+__global__ __launch_bounds__(1024, 4) void k_rsr_matvec1(
     const uint16_t *__restrict__ entries0, const uint16_t *__restrict__ codes0,
     const void *__restrict__ v, int C0, int n_in, int W, long long ldv,
     const int8_t *__restrict__ wsign0, const FoldArgs f, float sign0, const SecondPass a1,
@@ -633,11 +712,11 @@ __device__ __forceinline__ int sgn_digit(uint32_t c, int r) {
 // fpack[r][g][lane], r < k: byte u holds the weight of j = lane + 64 (4g + u) in row r:
 // r < m: sgn_r(j) - sgn_r((j+1) mod Tc) for j < Tc (class j); m <= r < k:
 // sgn_{r-m}(j) - sgn_{r-m}(j+1) for j < Q (entry E[Tc*j + Tc-1]); 0 past the end.
-// fshare[t] for every thread t of the workgroup: x = first E index of its level-1 share
-// | number of entries << 16 (0 for threads without a share), y = its class.
+// fshare[t] for every thread t of the workgroup: first E index of its level-1 share,
+// (class) + Tc * cnt1 * (part), or 0xffffffff for threads without a share.
 template <int BASE>
 __global__ void k_fold_tables(int k, FoldShape fs, int threads, uint32_t *__restrict__ fpack,
-                              uint2 *__restrict__ fshare) {
+                              uint32_t *__restrict__ fshare) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < k * fs.G * 64) {
         const int lane = t & 63, g = (t >> 6) % fs.G, r = (t >> 6) / fs.G;
@@ -656,12 +735,10 @@ __global__ void k_fold_tables(int k, FoldShape fs, int threads, uint32_t *__rest
         fpack[t] = pk;
     }
     if (t < threads) {
-        uint2 share = make_uint2(0u, 0u);
+        uint32_t share = 0xffffffffu;
         if (t < fs.Tc * fs.parts) {
             const int part = t / fs.Tc, cls = t - part * fs.Tc;
-            const int i0 = fs.ib[part], i1 = fs.ib[part + 1];
-            share.x = (uint32_t)(cls + fs.Tc * i0) | ((uint32_t)(i1 - i0) << 16);
-            share.y = (uint32_t)cls;
+            share = (uint32_t)(cls + fs.Tc * fs.cnt1 * part);
         }
         fshare[t] = share;
     }
@@ -726,8 +803,7 @@ void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int 
         if (parts < 1) parts = 1;
     }
     fs->parts = parts;
-    for (int j = 0; j <= 4; ++j)
-        fs->ib[j] = (j <= parts) ? (int)((long long)j * fs->Q / parts) : fs->Q;
+    fs->cnt1 = (fs->Q + parts - 1) / parts;
     const int span1 = fs->Tc * parts;
     const int span2 = fs->Q < threads ? fs->Q : threads;
     fs->nact = ((span1 > span2 ? span1 : span2) + 63) / 64;
@@ -741,8 +817,7 @@ void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int 
 }
 
 hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int W, uint32_t *fpack,
-                              uint32_t *fshare_words) {
-    uint2 *fshare = reinterpret_cast<uint2 *>(fshare_words);
+                              uint32_t *fshare) {
     const int nthreads = W * 64;
     const int rows = k * fs.G * 64;
     const int span = rows > nthreads ? rows : nthreads;
@@ -799,7 +874,7 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     x.nblocks = (int)h->nb;
     x.batch = batch;
     x.f.fpack = h->fpack;
-    x.f.fshare = reinterpret_cast<const uint2 *>(h->fshare);
+    x.f.fshare = h->fshare;
     x.f.k = h->k;
     x.f.P = (int)h->P;
     x.f.m = fs.m;
@@ -807,6 +882,7 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     x.f.Q = fs.Q;
     x.f.G = fs.G;
     x.f.parts = fs.parts;
+    x.f.cnt1 = fs.cnt1;
     x.o.out = out;
     x.o.ldo = ldo;
     x.o.n_out = (int)h->rows;
