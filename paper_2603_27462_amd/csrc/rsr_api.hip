@@ -61,9 +61,10 @@ int preprocess_dense(rsr_handle_s *h, const int8_t *M) {
     int rc = RSR_OK;
     int *err_flag = nullptr;
     int host_flag = 0;
-    const int64_t ntiles = (h->cols + 1023) / 1024;
-    h->row_bytes = ntiles * 256;
-    const size_t bytes = (size_t)((h->rows + 3) / 4) * 4 * h->row_bytes;
+    const int64_t ntiles = (h->cols + rsr::kDenseTileCols - 1) / rsr::kDenseTileCols;
+    h->row_bytes = ntiles * (rsr::kDenseTileCols / 4);
+    const size_t bytes =
+        (size_t)((h->rows + rsr::kDenseRows - 1) / rsr::kDenseRows) * rsr::kDenseRows * h->row_bytes;
     RSR_TRY(dev_alloc(&h->packed, bytes));
     RSR_TRY(dev_alloc(&err_flag, 1));
     RSR_TRY(hipMemsetAsync(err_flag, 0, sizeof(int), 0));
@@ -262,7 +263,8 @@ int rsr_get_offsets(rsr_handle_t h, int pass, uint32_t *host_off) {
 
 int rsr_get_packed(rsr_handle_t h, uint8_t *host_packed) {
     if (!good(h) || !host_packed || h->kind != RSR_DENSE_TERNARY_P2) return fail(RSR_EINVAL);
-    const int64_t ntiles = h->row_bytes / 256, ngroups = (h->rows + 3) / 4;
+    const int64_t ntiles = h->row_bytes / (rsr::kDenseTileCols / 4);
+    const int64_t ngroups = (h->rows + rsr::kDenseRows - 1) / rsr::kDenseRows;
     const size_t words = (size_t)(ngroups * ntiles * 256);
     std::vector<uint32_t> tiled(words);
     if (hipMemcpy(tiled.data(), h->packed, words * 4, hipMemcpyDeviceToHost) != hipSuccess)
@@ -271,12 +273,14 @@ int rsr_get_packed(rsr_handle_t h, uint8_t *host_packed) {
     const int64_t rb = (h->cols + 3) / 4;
     for (int64_t i = 0; i < h->rows * rb; ++i) host_packed[i] = 0;
     for (int64_t i = 0; i < h->rows; ++i) {
-        const int64_t G = i / 4, rr = i % 4;
+        const int64_t G = i / rsr::kDenseRows, rr = i % rsr::kDenseRows;
         for (int64_t j = 0; j < h->cols; ++j) {
-            const int64_t t = j / 1024, jj = j % 1024;
-            const int64_t i4 = jj / 256, lane = (jj % 256) / 4, s = jj % 4;
-            const uint32_t word = tiled[(size_t)(((G * ntiles + t) * 64 + lane) * 4 + rr)];
-            const uint32_t two = (word >> (2 * (i4 * 4 + s))) & 3u;
+            const int64_t t = j / rsr::kDenseTileCols, jj = j % rsr::kDenseTileCols;
+            const int64_t step = jj / 32, kq = (jj % 32) / 8, e = jj % 8;
+            const int64_t d = step / 2, p = (step % 2) * 4 + e / 2;
+            const int shift = (int)(((e & 1) ? 30 : 14) - 2 * p);
+            const uint32_t word = tiled[(size_t)(((G * ntiles + t) * 64 + (rr + 16 * kq)) * 4 + d)];
+            const uint32_t two = (word >> shift) & 3u;
             host_packed[i * rb + j / 4] |= (uint8_t)(two << (2 * (j % 4)));
         }
     }
@@ -295,13 +299,13 @@ int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch) {
     const int64_t vb = (v_dtype == RSR_BF16) ? 2 : 4;
     int64_t weight_side;
     if (h->kind == RSR_DENSE_TERNARY_P2) {
-        weight_side = (h->rows + 3) / 4 * 4 * h->row_bytes;
+        weight_side = (h->rows + rsr::kDenseRows - 1) / rsr::kDenseRows * rsr::kDenseRows * h->row_bytes;
     } else {
         weight_side = 0;
         for (int ps = 0; ps < h->npass; ++ps)
             weight_side += h->nb * (h->pass[ps].C * ((int64_t)rsr::kLoad * h->H * 2 + 64 * 2) +
                                     (int64_t)h->W * 16);
-        weight_side += (int64_t)h->k * h->fold.G * 256 + (int64_t)h->W * 64 * 8;
+        weight_side += (int64_t)h->k * h->fold.G * 256 + (int64_t)h->W * 64 * 4;
     }
     return weight_side + (int64_t)batch * (h->cols * vb + h->rows * 4);
 }

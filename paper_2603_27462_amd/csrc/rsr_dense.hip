@@ -3,40 +3,57 @@
 // Benchmarking Results).  No preprocessing beyond packing; every matrix entry
 // is decoded and multiplied.
 //
-// Kernel layout (tiled so that both the weight loads and the LDS reads of v
-// are contiguous across a wave): rows are taken in groups of 4, columns in
-// tiles of 1024.  For group G, tile t, lane l, one uint4 holds the dwords of
-// rows 4G..4G+3; bit field f (2 bits, two's complement: 00 = 0, 01 = +1,
-// 11 = -1) of each dword is column t*1024 + 256*(f/4) + 4*l + f%4.
+// The product is a dense contraction, so it runs on the matrix cores:
+// v_mfma_f32_16x16x32_bf16 with A = 16 rows x 32 columns of weights and B = the
+// matching 32 entries of v (the same in all 16 B columns; column 0 of the
+// result is read).  A 2-bit code (00 = 0, 01 = +1, 11 = -1) placed in the two
+// top bits of a bf16 is 0, +2.0 or -2.0, so one shift and one AND turn a dword
+// of 16 codes into a pair of A elements; the factor 2 is taken out of the
+// output scale.  float32 vectors are split exactly into three bf16 planes
+// (top, middle and bottom 8 mantissa bits) and take three MFMAs per step.
+//
+// Layout: [row group of 16][tile of 256 columns][lane][4 dwords], one 16-byte
+// load per lane and tile (1 KiB per wave).  Lane l holds row l%16 and the
+// column slices 8*(l/16).. of the tile's eight 32-column steps: dword d feeds
+// steps 2d and 2d+1; inside a dword, pair slot p (0..7) has its even column in
+// bits 14-2p.. and its odd column in bits 30-2p...
+#include "rsr_device.h"
 #include "rsr_internal.h"
 
 namespace rsr {
 
 namespace {
 
-constexpr int kTile = 1024;
+constexpr int kSlabTiles = 64;  // tiles of v staged in LDS at a time (16384 columns)
+constexpr int kDenseWaves = 8;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(256) void k_pack2_tiled(const int8_t *__restrict__ M, int64_t rows,
-                                                     int64_t cols, int ntiles,
+                                                     int64_t cols, int64_t ntiles,
                                                      uint32_t *__restrict__ tiled,
                                                      int *__restrict__ err_flag) {
-    const int64_t ngroups = (rows + 3) / 4;
+    const int64_t ngroups = (rows + kDenseRows - 1) / kDenseRows;
     const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (gid >= ngroups * ntiles * 256) return;
-    const int rr = (int)(gid & 3);
+    const int d = (int)(gid & 3);
     const int lane = (int)((gid >> 2) & 63);
     const int64_t gt = gid >> 8;
     const int64_t G = gt / ntiles, t = gt % ntiles;
-    const int64_t i = G * 4 + rr;
+    const int64_t i = G * kDenseRows + (lane & 15);
+    const int kq = lane >> 4;
     uint32_t word = 0;
     bool bad = false;
     if (i < rows) {
-        for (int f = 0; f < 16; ++f) {
-            const int64_t j = t * kTile + 256 * (f >> 2) + 4 * lane + (f & 3);
-            if (j < cols) {
-                const int m = M[i * cols + j];
-                if (m < -1 || m > 1) bad = true;
-                word |= ((uint32_t)m & 3u) << (2 * f);
+        for (int p = 0; p < 8; ++p) {
+            for (int hi = 0; hi < 2; ++hi) {
+                const int64_t j = t * kDenseTileCols + (2 * d + (p >> 2)) * 32 + 8 * kq + 2 * (p & 3) + hi;
+                if (j < cols) {
+                    const int m = M[i * cols + j];
+                    if (m < -1 || m > 1) bad = true;
+                    word |= ((uint32_t)m & 3u) << ((hi ? 30 : 14) - 2 * p);
+                }
             }
         }
     }
@@ -44,75 +61,128 @@ __global__ __launch_bounds__(256) void k_pack2_tiled(const int8_t *__restrict__ 
     tiled[gid] = word;
 }
 
+// Stages columns [c0, c0 + ncols) of v (zero past n_in) into LDS as bf16 planes of
+// `plane` bytes each: one plane for bf16 input, three for float32.
 template <typename VT>
-__device__ __forceinline__ float widen(VT x);
+__device__ __forceinline__ void stage_v(const VT *__restrict__ vg, int n_in, int c0, int ncols,
+                                        uint32_t plane, int tid, int nthreads);
+
 template <>
-__device__ __forceinline__ float widen<float>(float x) { return x; }
+__device__ __forceinline__ void stage_v<uint16_t>(const uint16_t *__restrict__ vg, int n_in, int c0,
+                                                  int ncols, uint32_t plane, int tid,
+                                                  int nthreads) {
+    (void)plane;
+    lds_u128 *l16 = reinterpret_cast<lds_u128 *>(static_cast<uintptr_t>(0));
+    const bool aligned = (reinterpret_cast<uintptr_t>(vg + c0) & 15) == 0;
+    const int full = aligned ? max(0, min(ncols, n_in - c0)) >> 3 : 0;  // whole 16-byte pieces
+    const u32x4 *v16 = reinterpret_cast<const u32x4 *>(vg + c0);
+    for (int j = tid; j < full; j += nthreads) l16[j] = v16[j];
+    for (int j = full * 8 + tid; j < ncols; j += nthreads)
+        lds_store_v<uint16_t>(j * 2, (c0 + j < n_in) ? vg[c0 + j] : (uint16_t)0);
+}
+
 template <>
-__device__ __forceinline__ float widen<uint16_t>(uint16_t x) {
-    return __uint_as_float((uint32_t)x << 16);
+__device__ __forceinline__ void stage_v<float>(const float *__restrict__ vg, int n_in, int c0,
+                                               int ncols, uint32_t plane, int tid, int nthreads) {
+    for (int j = tid; j < ncols; j += nthreads) {
+        const float x = (c0 + j < n_in) ? vg[c0 + j] : 0.0f;
+        // x = top + mid + bot exactly: each piece keeps 8 of the 24 significant bits
+        const uint32_t top = __float_as_uint(x) & 0xffff0000u;
+        const float r1 = x - __uint_as_float(top);
+        const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(mid);
+        lds_store_v<uint16_t>(j * 2, (uint16_t)(top >> 16));
+        lds_store_v<uint16_t>((int)plane + j * 2, (uint16_t)(mid >> 16));
+        lds_store_v<uint16_t>(2 * (int)plane + j * 2, (uint16_t)(__float_as_uint(r2) >> 16));
+    }
 }
 
-__device__ __forceinline__ float wave_sum(float x) {
+// One tile (16 rows x 256 columns) of one wave: eight MFMA steps (three MFMAs each for
+// float32 input).  vb: LDS byte address of this lane's slice of the tile's first step.
+template <int PLANES>
+__device__ __forceinline__ void tile_mfma(const u32x4 q, uint32_t vb, uint32_t plane, f32x4 &acc) {
+    const uint32_t w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
-    return x;
-}
-
-// sign-extended 2-bit field f of w, as float (-1, 0 or +1)
-__device__ __forceinline__ float field(uint32_t w, int f) {
-    return (float)(((int)(w << (30 - 2 * f))) >> 30);
-}
-
-// Workgroup = 4 waves = 2 row groups x 2 halves of the tile range.
-template <typename VT>
-__global__ __launch_bounds__(256) void k_dense_matvec(const uint4 *__restrict__ tiled, int ntiles,
-                                                      int n_in, int n_out, int ngroups,
-                                                      const void *__restrict__ v, long long ldv,
-                                                      float *__restrict__ out, long long ldo,
-                                                      float scale) {
-    extern __shared__ __align__(16) unsigned char smem[];
-    float *vf = reinterpret_cast<float *>(smem);       // [ntiles*1024], zero padded
-    float *red = vf + ntiles * kTile;                  // [4 waves][4 rows]
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const VT *vg = reinterpret_cast<const VT *>(v) + (long long)blockIdx.y * ldv;
-    for (int j = tid; j < ntiles * kTile; j += 256) vf[j] = (j < n_in) ? widen<VT>(vg[j]) : 0.0f;
-    __syncthreads();
-
-    const int rgl = w & 1, half = w >> 1;
-    const int G = blockIdx.x * 2 + rgl;
-    const int tmid = (ntiles + 1) / 2;
-    const int t0 = half ? tmid : 0, t1 = half ? ntiles : tmid;
-    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (G < ngroups) {
-        for (int t = t0; t < t1; ++t) {
-            const uint4 q = tiled[((long long)G * ntiles + t) * 64 + lane];
-            const uint32_t wq[4] = {q.x, q.y, q.z, q.w};
+    for (int d = 0; d < 4; ++d) {
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const float4 vv =
-                    *reinterpret_cast<const float4 *>(&vf[t * kTile + 256 * i4 + 4 * lane]);
-                const float vs[4] = {vv.x, vv.y, vv.z, vv.w};
+        for (int half = 0; half < 2; ++half) {
+            u32x4 a;
+            a.x = (w[d] << (8 * half)) & 0xc000c000u;
+            a.y = (w[d] << (8 * half + 2)) & 0xc000c000u;
+            a.z = (w[d] << (8 * half + 4)) & 0xc000c000u;
+            a.w = (w[d] << (8 * half + 6)) & 0xc000c000u;
+            const uint32_t at = vb + (uint32_t)(2 * d + half) * 64u;
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-#pragma unroll
-                    for (int rr = 0; rr < 4; ++rr)
-                        acc[rr] = fmaf(field(wq[rr], i4 * 4 + s), vs[s], acc[rr]);
-                }
+            for (int pl = 0; pl < PLANES; ++pl) {
+                const u32x4 b = *reinterpret_cast<lds_u128 *>(static_cast<uintptr_t>(at + pl * plane));
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a),
+                                                              __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
             }
         }
     }
+}
+
+// Workgroup = 8 waves = one group of 16 rows; the waves split the tiles of every slab.
+template <typename VT>
+__global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
+    const u32x4 *__restrict__ tiled, int ntiles, int n_in, int n_out, const void *__restrict__ v,
+    long long ldv, float *__restrict__ out, long long ldo, float scale) {
+    constexpr int PLANES = sizeof(VT) == 4 ? 3 : 1;
+    constexpr int nthreads = kDenseWaves * 64;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const VT *vg = reinterpret_cast<const VT *>(v) + (long long)blockIdx.y * ldv;
+    const int slab_cols = min(ntiles, kSlabTiles) * kDenseTileCols;
+    const uint32_t plane = (uint32_t)slab_cols * 2u;
+    const uint32_t red_at = plane * PLANES;  // float [8 waves][16 rows]
+    const u32x4 *wp = tiled + ((long long)blockIdx.x * ntiles) * 64 + lane;
+    const uint32_t lane_vb = (uint32_t)(lane >> 4) * 16u;
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+
+    for (int s0 = 0; s0 < ntiles; s0 += kSlabTiles) {
+        const int st = min(kSlabTiles, ntiles - s0);  // tiles in this slab
+        // this wave's tiles of the slab: [t0, t1)
+        const int t0 = s0 + (st * w) / kDenseWaves, t1 = s0 + (st * (w + 1)) / kDenseWaves;
+        // the first eight weight loads leave before v is staged
+        u32x4 q[8];
+        if (t1 > t0) {
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-        const float t = wave_sum(acc[rr]);
-        if (lane == 0) red[w * 4 + rr] = t;
+            for (int i = 0; i < 8; ++i)
+                q[i] = __builtin_nontemporal_load(&wp[(long long)min(t0 + i, t1 - 1) * 64]);
+        }
+        if (s0 > 0) __syncthreads();  // the previous slab is no longer read
+        stage_v<VT>(vg, n_in, s0 * kDenseTileCols, st * kDenseTileCols, plane, tid, nthreads);
+        __syncthreads();
+        for (int tb = t0; tb < t1; tb += 8) {
+            if (tb > t0) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    q[i] = __builtin_nontemporal_load(&wp[(long long)min(tb + i, t1 - 1) * 64]);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (tb + i < t1)
+                    tile_mfma<PLANES>(q[i], (uint32_t)(tb + i - s0) * (kDenseTileCols * 2) + lane_vb,
+                                      plane, acc);
+            }
+        }
+    }
+    // column 0 of the 16x16 result: lanes 0, 16, 32, 48 hold rows 4*(lane/16) .. +3
+    if ((lane & 15) == 0) {
+        const uint32_t at = red_at + (uint32_t)(w * 16 + (lane >> 4) * 4) * 4u;
+        *lds_float(at) = acc.x;
+        *lds_float(at + 4) = acc.y;
+        *lds_float(at + 8) = acc.z;
+        *lds_float(at + 12) = acc.w;
     }
     __syncthreads();
-    if (tid < 8) {
-        const int g = tid >> 2, rr = tid & 3;
-        const long long row = ((long long)blockIdx.x * 2 + g) * 4 + rr;
-        if (row < n_out)
-            out[(long long)blockIdx.y * ldo + row] = scale * (red[g * 4 + rr] + red[(g + 2) * 4 + rr]);
+    if (tid < kDenseRows) {
+        float sum = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kDenseWaves; ++i) sum += *lds_float(red_at + (uint32_t)(i * 16 + tid) * 4u);
+        const long long row = (long long)blockIdx.x * kDenseRows + tid;
+        // the weights were +-2
+        if (row < n_out) out[(long long)blockIdx.y * ldo + row] = (0.5f * scale) * sum;
     }
 }
 
@@ -121,28 +191,30 @@ hipError_t launch(const rsr_handle_s *h, const void *v, float scale, float *out,
                   int64_t ldv, int64_t ldo, hipStream_t stream) {
     static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
     auto kern = k_dense_matvec<VT>;
-    const int ntiles = (int)(h->row_bytes / 256);
-    const int ngroups = (int)((h->rows + 3) / 4);
-    const size_t lds = (size_t)ntiles * kTile * 4 + 64;
+    const int ntiles = (int)(h->row_bytes / (kDenseTileCols / 4));
+    const int ngroups = (int)((h->rows + kDenseRows - 1) / kDenseRows);
+    const int planes = sizeof(VT) == 4 ? 3 : 1;
+    const size_t slab_cols = (size_t)(ntiles < kSlabTiles ? ntiles : kSlabTiles) * kDenseTileCols;
+    const size_t lds = slab_cols * 2 * planes + kDenseWaves * 16 * 4;
     if (lds > attr_bytes) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_bytes = lds;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)((ngroups + 1) / 2), (unsigned)batch), dim3(256), lds,
-                       stream, reinterpret_cast<const uint4 *>(h->packed), ntiles, (int)h->cols,
-                       (int)h->rows, ngroups, v, (long long)ldv, out, (long long)ldo, scale);
+    hipLaunchKernelGGL(kern, dim3((unsigned)ngroups, (unsigned)batch), dim3(kDenseWaves * 64), lds,
+                       stream, reinterpret_cast<const u32x4 *>(h->packed), ntiles, (int)h->cols,
+                       (int)h->rows, v, (long long)ldv, out, (long long)ldo, scale);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// packed: [ceil(rows/4)][row_bytes/256 tiles][64 lanes][4 rows] dwords; row_bytes = tiles*256.
+// packed: [ceil(rows/16)][row_bytes/64 tiles][64 lanes][4] dwords; row_bytes = tiles*64.
 hipError_t launch_pack2(const int8_t *M, int64_t rows, int64_t cols, int64_t row_bytes,
                         uint8_t *packed, int *err_flag) {
-    const int ntiles = (int)(row_bytes / 256);
-    const int64_t total = (rows + 3) / 4 * ntiles * 256;
+    const int64_t ntiles = row_bytes / (kDenseTileCols / 4);
+    const int64_t total = (rows + kDenseRows - 1) / kDenseRows * ntiles * 256;
     hipLaunchKernelGGL(k_pack2_tiled, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, 0, M,
                        rows, cols, ntiles, reinterpret_cast<uint32_t *>(packed), err_flag);
     return hipGetLastError();

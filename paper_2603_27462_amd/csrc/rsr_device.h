@@ -1,6 +1,6 @@
 // Device-side building blocks of the RSR multiply kernels (gfx950, wave64): raw LDS
 // addressing, DPP scans, and the per-entry gather / tail-store steps written out
-// as instructions.  Included only by rsr_matvec.hip.
+// as instructions.  Included by the kernel translation units only.
 #pragma once
 
 #include "rsr_internal.h"

@@ -14,6 +14,8 @@ constexpr int kMaxCols = 32766;        // index 'cols' is the zero slot and must
 constexpr int kSmallCols = 16383;      // up to here an entry is tail<<15 | idx<<1
 constexpr int kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
 constexpr int kLdsMisc = 1024;         // wave-total terms of the scatter phase
+constexpr int kDenseRows = 16;         // dense comparison kernel: rows per workgroup
+constexpr int kDenseTileCols = 256;    // and columns per 16-byte-per-lane tile
 
 // One pass of an RSR handle (binary, M+, M- or fused).
 //
@@ -57,7 +59,7 @@ struct rsr_handle_s {
     rsr::FoldShape fold;
     uint32_t *fpack = nullptr;   // scatter-phase weights, four per dword: [k][fold.G][64]
     uint32_t *fshare = nullptr;  // first entry of the level-1 share of every thread [W*64]
-    uint8_t *packed = nullptr;   // dense kind: [rows][row_bytes], row_bytes % 16 == 0
+    uint8_t *packed = nullptr;   // dense kind: [rows/16][tiles][64 lanes][16 bytes], row_bytes = 64 tiles
     int64_t row_bytes = 0;
 };
 
