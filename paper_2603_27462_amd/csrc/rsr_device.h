@@ -88,49 +88,49 @@ __device__ __forceinline__ void lds_wait(uint32_t (&g)[8]) {
                  : "n"(N));
 }
 
-// If the entry is a tail: E[ptr] = base + s, ptr += 4.  Small encoding: the tail
-// flag is the sign of the 16-bit entry (low half: 16-bit compare on d; high
-// half: sign of the dword).
-template <int ENC, int HALF>
-__device__ __forceinline__ void tail_store(uint32_t d, float base, float s, uint32_t &ptr) {
+// The two entries of dword d: if an entry is a tail, E[ptr] = base + s, ptr += 4.
+// The compare writes the execution mask itself (all 64 lanes are live when this runs:
+// the workgroup size is a multiple of 64 and the caller is in wave-uniform control
+// flow), and the mask is set back to all ones afterwards.  Small encoding: the tail
+// flag is the sign of the 16-bit entry (low half: 16-bit compare; high half: sign of
+// the dword).  Big encoding: bit 0 / bit 16, moved to the sign by a shift.
+template <int ENC>
+__device__ __forceinline__ void tail_store2(uint32_t d, float base, float s0, float s1,
+                                            uint32_t &ptr) {
     float t;
-    uint64_t saved;
     if (ENC == kEncSmall) {
-        if (HALF)
-            asm volatile(
-                "v_cmp_gt_i32 vcc, 0, %[d]\n\t"
-                "s_and_saveexec_b64 %[sv], vcc\n\t"
-                "v_add_f32 %[t], %[b], %[s]\n\t"
-                "ds_write_b32 %[p], %[t]\n\t"
-                "v_add_u32 %[p], 4, %[p]\n\t"
-                "s_mov_b64 exec, %[sv]"
-                : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
-                : [d] "v"(d), [b] "v"(base), [s] "v"(s)
-                : "vcc", "scc", "memory");
-        else
-            asm volatile(
-                "v_cmp_gt_i16 vcc, 0, %[d]\n\t"
-                "s_and_saveexec_b64 %[sv], vcc\n\t"
-                "v_add_f32 %[t], %[b], %[s]\n\t"
-                "ds_write_b32 %[p], %[t]\n\t"
-                "v_add_u32 %[p], 4, %[p]\n\t"
-                "s_mov_b64 exec, %[sv]"
-                : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
-                : [d] "v"(d), [b] "v"(base), [s] "v"(s)
-                : "vcc", "scc", "memory");
-    } else {
-        // idx<<1 | tail: bit 0 (low half) or bit 16 (high half)
         asm volatile(
-            "v_bfe_i32 %[t], %[d], %[bit], 1\n\t"
-            "v_cmp_gt_i32 vcc, 0, %[t]\n\t"
-            "s_and_saveexec_b64 %[sv], vcc\n\t"
-            "v_add_f32 %[t], %[b], %[s]\n\t"
+            "v_cmpx_gt_i16 vcc, 0, %[d]\n\t"
+            "v_add_f32 %[t], %[b], %[s0]\n\t"
             "ds_write_b32 %[p], %[t]\n\t"
             "v_add_u32 %[p], 4, %[p]\n\t"
-            "s_mov_b64 exec, %[sv]"
-            : [p] "+v"(ptr), [t] "=&v"(t), [sv] "=&s"(saved)
-            : [d] "v"(d), [b] "v"(base), [s] "v"(s), [bit] "n"(HALF ? 16 : 0)
-            : "vcc", "scc", "memory");
+            "s_mov_b64 exec, -1\n\t"
+            "v_cmpx_gt_i32 vcc, 0, %[d]\n\t"
+            "v_add_f32 %[t], %[b], %[s1]\n\t"
+            "ds_write_b32 %[p], %[t]\n\t"
+            "v_add_u32 %[p], 4, %[p]\n\t"
+            "s_mov_b64 exec, -1"
+            : [p] "+v"(ptr), [t] "=&v"(t)
+            : [d] "v"(d), [b] "v"(base), [s0] "v"(s0), [s1] "v"(s1)
+            : "vcc", "memory");
+    } else {
+        uint32_t u;
+        asm volatile(
+            "v_lshlrev_b32 %[u], 31, %[d]\n\t"
+            "v_cmpx_gt_i32 vcc, 0, %[u]\n\t"
+            "v_add_f32 %[t], %[b], %[s0]\n\t"
+            "ds_write_b32 %[p], %[t]\n\t"
+            "v_add_u32 %[p], 4, %[p]\n\t"
+            "s_mov_b64 exec, -1\n\t"
+            "v_lshlrev_b32 %[u], 15, %[d]\n\t"
+            "v_cmpx_gt_i32 vcc, 0, %[u]\n\t"
+            "v_add_f32 %[t], %[b], %[s1]\n\t"
+            "ds_write_b32 %[p], %[t]\n\t"
+            "v_add_u32 %[p], 4, %[p]\n\t"
+            "s_mov_b64 exec, -1"
+            : [p] "+v"(ptr), [t] "=&v"(t), [u] "=&v"(u)
+            : [d] "v"(d), [b] "v"(base), [s0] "v"(s0), [s1] "v"(s1)
+            : "vcc", "memory");
     }
 }
 

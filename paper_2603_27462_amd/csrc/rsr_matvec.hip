@@ -65,7 +65,7 @@ struct OutArgs {
 #define RSR_STAMP(i)                                                          \
     do {                                                                      \
         if (o.stamps && threadIdx.x == 0 && blockIdx.y == 0)                  \
-            o.stamps[blockIdx.x * 8 + (i)] = (long long)__builtin_readcyclecounter(); \
+            o.stamps[blockIdx.x * 16 + (i)] = (long long)__builtin_readcyclecounter(); \
     } while (0)
 #else
 #define RSR_STAMP(i) do { } while (0)
@@ -407,8 +407,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
                 for (int h = 0; h < H; ++h) {
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        tail_store<ENC, 0>(d[h][j], base, s[h][2 * j], ptr);
-                        tail_store<ENC, 1>(d[h][j], base, s[h][2 * j + 1], ptr);
+                        tail_store2<ENC>(d[h][j], base, s[h][2 * j], s[h][2 * j + 1], ptr);
                     }
                 }
                 run += lane63(incl);
@@ -555,6 +554,12 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     __syncthreads();
     RSR_STAMP(1);
     RSR_STOP(1);
+#ifdef RSR_PHASE_TIMING
+    if (o.stop_after >= 100) {  // experiment: stagger the odd waves
+        const int n = o.stop_after - 100;
+        if (w & 1) for (int i = 0; i < n; ++i) __builtin_amdgcn_s_sleep(2);
+    }
+#endif
 
     // ---- gather + aggregate -------------------------------------------------------------
     float total = 0.0f;
@@ -583,7 +588,9 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
                 }
                 lds_wait<8>(g[h]);
             } else {
+                RSR_STAMP(8);
                 lds_wait<0>(g[h]);
+                RSR_STAMP(9);
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -591,15 +598,16 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
                 s[h][i] = prev;
             }
         }
+        RSR_STAMP(10);
         const float incl = wave_inclusive_scan(prev);
         const float base = wave_shift_right(incl);
+        RSR_STAMP(11);
         uint32_t ptr = e_at + code * 4u;
 #pragma unroll
         for (int h = 0; h < H; ++h) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                tail_store<ENC, 0>(d[h][j], base, s[h][2 * j], ptr);
-                tail_store<ENC, 1>(d[h][j], base, s[h][2 * j + 1], ptr);
+                tail_store2<ENC>(d[h][j], base, s[h][2 * j], s[h][2 * j + 1], ptr);
             }
         }
         total = lane63(incl);
