@@ -202,6 +202,11 @@ def main():
             "warm_us_per_step": ms_dw * 1e3 / args.steps,
             "weight_sets": dsets, "max_abs_err_vs_f64": derr,
             "kernel": rsr.rsr_kernel_name(dh[0], rsr.RSR_BF16),
+            "algorithmic_bytes_per_launch": dbytes,
+            "frac_hbm_peak": dbytes / (ms_d * 1e-3 / args.steps) / 1e9 / HBM_PEAK_GBS,
+            # 16x16x32 bf16 MFMA steps: every matrix entry times the 16 B columns, 2 flops
+            "mfma_TFLOPs": rows * cols * 16 * 2 / (ms_d * 1e-3 / args.steps) / 1e12,
+            "frac_mfma_bf16_peak": rows * cols * 16 * 2 / (ms_d * 1e-3 / args.steps) / 2.5e15,
         }
         result["speedup_vs_dense_packed2"] = ms_d / ms
 
