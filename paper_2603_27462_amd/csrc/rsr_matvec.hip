@@ -554,12 +554,6 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     __syncthreads();
     RSR_STAMP(1);
     RSR_STOP(1);
-#ifdef RSR_PHASE_TIMING
-    if (o.stop_after >= 100) {  // experiment: stagger the odd waves
-        const int n = o.stop_after - 100;
-        if (w & 1) for (int i = 0; i < n; ++i) __builtin_amdgcn_s_sleep(2);
-    }
-#endif
 
     // ---- gather + aggregate -------------------------------------------------------------
     float total = 0.0f;
@@ -631,6 +625,12 @@ __global__ __launch_bounds__(1024, 4) void k_rsr_matvec1(
     const int8_t *__restrict__ wsign0, const FoldArgs f, float sign0, const SecondPass a1,
     const OutArgs o) {
     RSR_STAMP(0);
+#ifdef RSR_PHASE_TIMING
+    if (o.stamps && threadIdx.x == 0 && blockIdx.y == 0) {  // where the workgroup runs
+        o.stamps[blockIdx.x * 16 + 12] = __builtin_amdgcn_s_getreg((4) | (0 << 6) | (31 << 11));   // HW_ID
+        o.stamps[blockIdx.x * 16 + 13] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));  // XCC_ID
+    }
+#endif
     single_pass<VT, H, ENC, true>(entries0, codes0, wsign0, C0, sign0, v, ldv, n_in, W, f, o.out,
                                   o.ldo, o.n_out, o.scale, o);
     if (NPASS == 2) {
