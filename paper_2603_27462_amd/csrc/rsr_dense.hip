@@ -10,7 +10,8 @@
 // top bits of a bf16 is 0, +2.0 or -2.0, so one shift and one AND turn a dword
 // of 16 codes into a pair of A elements; the factor 2 is taken out of the
 // output scale.  float32 vectors are split exactly into three bf16 planes
-// (top, middle and bottom 8 mantissa bits) and take three MFMAs per step.
+// (top, middle and bottom 8 mantissa bits) and take three MFMAs per step.  A batch
+// of vectors fills the B columns: up to 16 vectors cost one pass over the weights.
 //
 // Layout: [row group of 16][tile of 256 columns][lane][4 dwords], one 16-byte
 // load per lane and tile (1 KiB per wave).  Lane l holds row l%16 and the
@@ -61,29 +62,30 @@ __global__ __launch_bounds__(256) void k_pack2_tiled(const int8_t *__restrict__ 
     tiled[gid] = word;
 }
 
-// Stages columns [c0, c0 + ncols) of v (zero past n_in) into LDS as bf16 planes of
-// `plane` bytes each: one plane for bf16 input, three for float32.
+// Stages columns [c0, c0 + ncols) of one vector (zero past n_in) into LDS at byte address
+// `at` as bf16 planes of `plane` bytes each: one plane for bf16 input, three for float32.
 template <typename VT>
 __device__ __forceinline__ void stage_v(const VT *__restrict__ vg, int n_in, int c0, int ncols,
-                                        uint32_t plane, int tid, int nthreads);
+                                        uint32_t at, uint32_t plane, int tid, int nthreads);
 
 template <>
 __device__ __forceinline__ void stage_v<uint16_t>(const uint16_t *__restrict__ vg, int n_in, int c0,
-                                                  int ncols, uint32_t plane, int tid,
+                                                  int ncols, uint32_t at, uint32_t plane, int tid,
                                                   int nthreads) {
     (void)plane;
-    lds_u128 *l16 = reinterpret_cast<lds_u128 *>(static_cast<uintptr_t>(0));
+    lds_u128 *l16 = reinterpret_cast<lds_u128 *>(static_cast<uintptr_t>(at));
     const bool aligned = (reinterpret_cast<uintptr_t>(vg + c0) & 15) == 0;
     const int full = aligned ? max(0, min(ncols, n_in - c0)) >> 3 : 0;  // whole 16-byte pieces
     const u32x4 *v16 = reinterpret_cast<const u32x4 *>(vg + c0);
     for (int j = tid; j < full; j += nthreads) l16[j] = v16[j];
     for (int j = full * 8 + tid; j < ncols; j += nthreads)
-        lds_store_v<uint16_t>(j * 2, (c0 + j < n_in) ? vg[c0 + j] : (uint16_t)0);
+        lds_store_v<uint16_t>((int)at + j * 2, (c0 + j < n_in) ? vg[c0 + j] : (uint16_t)0);
 }
 
 template <>
 __device__ __forceinline__ void stage_v<float>(const float *__restrict__ vg, int n_in, int c0,
-                                               int ncols, uint32_t plane, int tid, int nthreads) {
+                                               int ncols, uint32_t at, uint32_t plane, int tid,
+                                               int nthreads) {
     for (int j = tid; j < ncols; j += nthreads) {
         const float x = (c0 + j < n_in) ? vg[c0 + j] : 0.0f;
         // x = top + mid + bot exactly: each piece keeps 8 of the 24 significant bits
@@ -91,9 +93,9 @@ __device__ __forceinline__ void stage_v<float>(const float *__restrict__ vg, int
         const float r1 = x - __uint_as_float(top);
         const uint32_t mid = __float_as_uint(r1) & 0xffff0000u;
         const float r2 = r1 - __uint_as_float(mid);
-        lds_store_v<uint16_t>(j * 2, (uint16_t)(top >> 16));
-        lds_store_v<uint16_t>((int)plane + j * 2, (uint16_t)(mid >> 16));
-        lds_store_v<uint16_t>(2 * (int)plane + j * 2, (uint16_t)(__float_as_uint(r2) >> 16));
+        lds_store_v<uint16_t>((int)at + j * 2, (uint16_t)(top >> 16));
+        lds_store_v<uint16_t>((int)(at + plane) + j * 2, (uint16_t)(mid >> 16));
+        lds_store_v<uint16_t>((int)(at + 2 * plane) + j * 2, (uint16_t)(__float_as_uint(r2) >> 16));
     }
 }
 
@@ -122,25 +124,33 @@ __device__ __forceinline__ void tile_mfma(const u32x4 q, uint32_t vb, uint32_t p
     }
 }
 
-// Workgroup = 8 waves = one group of 16 rows; the waves split the tiles of every slab.
+// Workgroup = 8 waves = one group of 16 rows times up to 16 vectors (the B columns of the
+// MFMA); the waves split the tiles of every slab.  LDS: vector n at n * vstride (planes
+// back to back; the stride is padded by 64 bytes so that the 16-byte reads of the 64
+// lanes -- 16 vectors x 4 column slices -- fall on distinct banks), then the partial
+// results, float [8 waves][16 vectors][16 rows].
 template <typename VT>
 __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
-    const u32x4 *__restrict__ tiled, int ntiles, int n_in, int n_out, const void *__restrict__ v,
-    long long ldv, float *__restrict__ out, long long ldo, float scale) {
+    const u32x4 *__restrict__ tiled, int ntiles, int slab_tiles, int n_in, int n_out,
+    const void *__restrict__ v, long long ldv, int batch, int nv, float *__restrict__ out,
+    long long ldo, float scale) {
     constexpr int PLANES = sizeof(VT) == 4 ? 3 : 1;
     constexpr int nthreads = kDenseWaves * 64;
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const VT *vg = reinterpret_cast<const VT *>(v) + (long long)blockIdx.y * ldv;
-    const int slab_cols = min(ntiles, kSlabTiles) * kDenseTileCols;
-    const uint32_t plane = (uint32_t)slab_cols * 2u;
-    const uint32_t red_at = plane * PLANES;  // float [8 waves][16 rows]
+    const int vec0 = blockIdx.y * nv, nvh = min(nv, batch - vec0);  // this workgroup's vectors
+    const VT *vg = reinterpret_cast<const VT *>(v) + (long long)vec0 * ldv;
+    const uint32_t plane = (uint32_t)slab_tiles * kDenseTileCols * 2u;
+    const uint32_t vstride = plane * PLANES + 64u;
+    const uint32_t red_at = vstride * (uint32_t)nv;
     const u32x4 *wp = tiled + ((long long)blockIdx.x * ntiles) * 64 + lane;
-    const uint32_t lane_vb = (uint32_t)(lane >> 4) * 16u;
+    // B column lane%16 is vector lane%16 (columns without a vector repeat vector 0)
+    const int col = lane & 15;
+    const uint32_t lane_vb = (uint32_t)(col < nvh ? col : 0) * vstride + (uint32_t)(lane >> 4) * 16u;
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 
-    for (int s0 = 0; s0 < ntiles; s0 += kSlabTiles) {
-        const int st = min(kSlabTiles, ntiles - s0);  // tiles in this slab
+    for (int s0 = 0; s0 < ntiles; s0 += slab_tiles) {
+        const int st = min(slab_tiles, ntiles - s0);  // tiles in this slab
         // this wave's tiles of the slab: [t0, t1)
         const int t0 = s0 + (st * w) / kDenseWaves, t1 = s0 + (st * (w + 1)) / kDenseWaves;
         // the first eight weight loads leave before v is staged
@@ -151,7 +161,9 @@ __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
                 q[i] = __builtin_nontemporal_load(&wp[(long long)min(t0 + i, t1 - 1) * 64]);
         }
         if (s0 > 0) __syncthreads();  // the previous slab is no longer read
-        stage_v<VT>(vg, n_in, s0 * kDenseTileCols, st * kDenseTileCols, plane, tid, nthreads);
+        for (int n = 0; n < nvh; ++n)
+            stage_v<VT>(vg + (long long)n * ldv, n_in, s0 * kDenseTileCols, st * kDenseTileCols,
+                        (uint32_t)n * vstride, plane, tid, nthreads);
         __syncthreads();
         for (int tb = t0; tb < t1; tb += 8) {
             if (tb > t0) {
@@ -167,24 +179,28 @@ __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
             }
         }
     }
-    // column 0 of the 16x16 result: lanes 0, 16, 32, 48 hold rows 4*(lane/16) .. +3
-    if ((lane & 15) == 0) {
-        const uint32_t at = red_at + (uint32_t)(w * 16 + (lane >> 4) * 4) * 4u;
+    // the 16x16 result: lane holds column lane%16, rows 4*(lane/16) .. +3
+    {
+        const uint32_t at = red_at + (uint32_t)((w * 16 + col) * 16 + (lane >> 4) * 4) * 4u;
         *lds_float(at) = acc.x;
         *lds_float(at + 4) = acc.y;
         *lds_float(at + 8) = acc.z;
         *lds_float(at + 12) = acc.w;
     }
     __syncthreads();
-    if (tid < kDenseRows) {
+    if (tid < kDenseRows * 16) {
+        const int n = tid >> 4, r = tid & 15;
         float sum = 0.0f;
 #pragma unroll
-        for (int i = 0; i < kDenseWaves; ++i) sum += *lds_float(red_at + (uint32_t)(i * 16 + tid) * 4u);
-        const long long row = (long long)blockIdx.x * kDenseRows + tid;
+        for (int i = 0; i < kDenseWaves; ++i)
+            sum += *lds_float(red_at + (uint32_t)((i * 16 + n) * 16 + r) * 4u);
+        const long long row = (long long)blockIdx.x * kDenseRows + r;
         // the weights were +-2
-        if (row < n_out) out[(long long)blockIdx.y * ldo + row] = (0.5f * scale) * sum;
+        if (n < nvh && row < n_out) out[(long long)(vec0 + n) * ldo + row] = (0.5f * scale) * sum;
     }
 }
+
+constexpr size_t kDenseLdsBudget = 150 * 1024;
 
 template <typename VT>
 hipError_t launch(const rsr_handle_s *h, const void *v, float scale, float *out, int batch,
@@ -194,17 +210,30 @@ hipError_t launch(const rsr_handle_s *h, const void *v, float scale, float *out,
     const int ntiles = (int)(h->row_bytes / (kDenseTileCols / 4));
     const int ngroups = (int)((h->rows + kDenseRows - 1) / kDenseRows);
     const int planes = sizeof(VT) == 4 ? 3 : 1;
-    const size_t slab_cols = (size_t)(ntiles < kSlabTiles ? ntiles : kSlabTiles) * kDenseTileCols;
-    const size_t lds = slab_cols * 2 * planes + kDenseWaves * 16 * 4;
+    // vectors per workgroup (the weights are read once for all of them) and the slab of
+    // columns staged at a time: as many vectors as keep a slab of at least 8 tiles in LDS
+    auto slab_for = [&](int nv) {
+        const size_t per_tile = (size_t)nv * planes * kDenseTileCols * 2;
+        const size_t fit = (kDenseLdsBudget - (size_t)nv * 64) / per_tile;
+        return (int)(fit < (size_t)kSlabTiles ? fit : (size_t)kSlabTiles);
+    };
+    int nv = batch < 16 ? batch : 16;
+    while (nv > 1 && slab_for(nv) < 8 && slab_for(nv) < ntiles) nv = (nv + 1) / 2;
+    int slab_tiles = slab_for(nv);
+    if (slab_tiles > ntiles) slab_tiles = ntiles;
+    if (slab_tiles < 1) slab_tiles = 1;
+    const size_t lds = (size_t)nv * ((size_t)slab_tiles * kDenseTileCols * 2 * planes + 64) +
+                       (size_t)kDenseWaves * 16 * 16 * 4;
     if (lds > attr_bytes) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         attr_bytes = lds;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)ngroups, (unsigned)batch), dim3(kDenseWaves * 64), lds,
-                       stream, reinterpret_cast<const u32x4 *>(h->packed), ntiles, (int)h->cols,
-                       (int)h->rows, v, (long long)ldv, out, (long long)ldo, scale);
+    hipLaunchKernelGGL(kern, dim3((unsigned)ngroups, (unsigned)((batch + nv - 1) / nv)),
+                       dim3(kDenseWaves * 64), lds, stream,
+                       reinterpret_cast<const u32x4 *>(h->packed), ntiles, slab_tiles, (int)h->cols,
+                       (int)h->rows, v, (long long)ldv, batch, nv, out, (long long)ldo, scale);
     return hipGetLastError();
 }
 

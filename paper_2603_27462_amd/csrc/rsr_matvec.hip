@@ -57,6 +57,8 @@ struct OutArgs {
     long long ldo;
     int n_out;
     float scale;
+    int batch;          // number of vectors
+    int vper;           // vectors one workgroup handles, one after the other
     long long *stamps;  // [blocks][8] shader-clock stamps of thread 0 (profiling builds only)
     int stop_after;     // profiling builds only: leave the kernel after this phase (0 = never)
 };
@@ -280,7 +282,7 @@ __device__ __forceinline__ void load_group(const uint4 *ep, const uint16_t *cp, 
 // LDS and the output rows are overwritten; otherwise the pass adds to them.
 template <typename VT, int H, int ENC, bool FIRST>
 __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long long ldv, int n_in,
-                                         int W, const FoldArgs &f, const OutArgs &o) {
+                                         int W, const FoldArgs &f, const OutArgs &o, int vec) {
     constexpr int PF = 4 / H;  // chunks requested together (16 dwords per lane)
     // LDS (byte addresses): v (n_in + zero slot) | wave-total terms | E[P] | red[k][fold threads]
     const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
@@ -316,7 +318,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
         // stage v into LDS (16-byte copies when the source allows it); requested
         // before the stream so that it arrives first
         const unsigned char *vg = reinterpret_cast<const unsigned char *>(v) +
-                                  (long long)blockIdx.y * ldv * (long long)sizeof(VT);
+                                  (long long)vec * ldv * (long long)sizeof(VT);
         const int nbytes = n_in * (int)sizeof(VT);
         if ((reinterpret_cast<uintptr_t>(vg) & 15) == 0) {
             const int n16 = nbytes >> 4;
@@ -431,7 +433,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long 
 
     // ---- scatter ----------------------------------------------------------------
     scatter_phase<FIRST>(sa, sp, wpre, corr_at, e_at, c1_at, W, w, lane, tid,
-                         o.scale * a.sign, o.out + (long long)blockIdx.y * o.ldo + b * f.k,
+                         o.scale * a.sign, o.out + (long long)vec * o.ldo + b * f.k,
                          (long long)o.n_out - b * f.k, o);
 }
 
@@ -441,10 +443,10 @@ __global__ __launch_bounds__(1024) void k_rsr_matvec(const PassArgs a0, const vo
                                                      const FoldArgs f, const PassArgs a1,
                                                      const OutArgs o) {
     RSR_STAMP(0);
-    run_pass<VT, H, ENC, true>(a0, v, ldv, n_in, W, f, o);
+    run_pass<VT, H, ENC, true>(a0, v, ldv, n_in, W, f, o, (int)blockIdx.y);
     if (NPASS == 2) {
         __syncthreads();
-        run_pass<VT, H, ENC, false>(a1, v, ldv, n_in, W, f, o);
+        run_pass<VT, H, ENC, false>(a1, v, ldv, n_in, W, f, o, (int)blockIdx.y);
     }
     RSR_STAMP(7);
 }
@@ -462,13 +464,15 @@ struct SecondPass {
     float sign;
 };
 
-template <typename VT, int H, int ENC, bool FIRST>
+template <typename VT, int H, int ENC, bool FIRST, bool MULTI>
 __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries,
                                             const uint16_t *__restrict__ codes,
                                             const int8_t *__restrict__ wsign, int C, float sign,
                                             const void *__restrict__ v, long long ldv, int n_in,
                                             int W, const FoldArgs &f, float *out, long long ldo,
-                                            int n_out, float scale, const OutArgs &o) {
+                                            int n_out, float scale, const OutArgs &o, int vec0,
+                                            int nvec_arg) {
+    const int nvec = MULTI ? nvec_arg : 1;
     const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
     const uint32_t corr_at = vbytes;                    // float [16 waves][16 rows]
     const uint32_t e_at = vbytes + kLdsMisc;            // float [P]
@@ -487,11 +491,13 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     const uint2 share = make_uint2(f.fshare[tid], 0u);
     const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
     const int8_t wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
-    const unsigned char *vg = reinterpret_cast<const unsigned char *>(v) +
-                              (long long)blockIdx.y * ldv * (long long)sizeof(VT);
+    // vectors vec0 .. vec0+nvec-1 are multiplied one after the other with the same stream
+    // registers (nvec > 1 only in the first pass of one-pass kinds)
+    const long long vstride = ldv * (long long)sizeof(VT);
+    const unsigned char *vg = reinterpret_cast<const unsigned char *>(v) + (long long)vec0 * vstride;
     const int nbytes = n_in * (int)sizeof(VT);
     const int n16 = nbytes >> 4;
-    const bool v_aligned = (reinterpret_cast<uintptr_t>(vg) & 15) == 0;
+    const bool v_aligned = (reinterpret_cast<uintptr_t>(vg) & 15) == 0 && (nvec == 1 || (vstride & 15) == 0);
     const u32x4 *v16 = reinterpret_cast<const u32x4 *>(vg);
     lds_u128 *l16 = reinterpret_cast<lds_u128 *>(static_cast<uintptr_t>(0));
     u32x4 s0, s1, s2, s3;
@@ -518,7 +524,7 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
 
     // ---- work that needs no stream data, done while the loads are in flight ----------------
     ScatterPrep sp;
-    prepare_scatter(sp, sa, share, wpre, corr_at, e_at, c1_at, W, w, lane, tid);
+    if (!MULTI) prepare_scatter(sp, sa, share, wpre, corr_at, e_at, c1_at, W, w, lane, tid);
     float wsg = (float)wsg8;
     pin(wsg);
     uint32_t g[H][8];  // gather targets: for bf16 the low halves must be zero
@@ -531,7 +537,7 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         }
     if (tid < f.Tc) *lds_float(z_at + (uint32_t)tid * 4u) = 0.0f;
 
-    // ---- stage v --------------------------------------------------------------------------
+    // ---- stage v (the first vector comes from the registers requested above) --------------
     if (FIRST) {
         if (v_aligned) {
             if (n16 > 0) {
@@ -550,10 +556,27 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         }
         if (tid == 0) lds_store_v<VT>(nbytes, VT(0));
     }
+    for (int vi = 0; vi < nvec; ++vi) {
+    if (MULTI && FIRST && vi > 0) {
+        // later vectors: every wave is past the gather phase of the previous one
+        if (v_aligned) {
+            for (int j = tid; j < n16; j += nthreads) l16[j] = v16[j];
+            for (int j = (n16 << 4) + tid * (int)sizeof(VT); j < nbytes;
+                 j += nthreads * (int)sizeof(VT))
+                lds_store_v<VT>(j, *reinterpret_cast<const VT *>(vg + j));
+        } else {
+            for (int j = tid * (int)sizeof(VT); j < nbytes; j += nthreads * (int)sizeof(VT))
+                lds_store_v<VT>(j, *reinterpret_cast<const VT *>(vg + j));
+        }
+    }
     if (tid == 0) *lds_float(e_at) = 0.0f;
     __syncthreads();
     RSR_STAMP(1);
     RSR_STOP(1);
+    if (MULTI && FIRST) {  // from here on vg is the next vector
+        vg += vstride;
+        v16 = reinterpret_cast<const u32x4 *>(vg);
+    }
 
     // ---- gather + aggregate -------------------------------------------------------------
     float total = 0.0f;
@@ -614,11 +637,23 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     RSR_STOP(2);
 
     // ---- scatter ----------------------------------------------------------------------
+    // (with several vectors the registers are needed for the stream: constants are made here)
+    if (MULTI) {
+        // opaque copies, so that the constants are recomputed here rather than kept alive
+        int tid_i = tid;
+        uint2 share_i = share;
+        uint32_t wpre_i = wpre;
+        pin(tid_i);
+        pin(share_i.x);
+        pin(wpre_i);
+        prepare_scatter(sp, sa, share_i, wpre_i, corr_at, e_at, c1_at, W, w, tid_i & 63, tid_i);
+    }
     scatter_phase<FIRST>(sa, sp, wpre, corr_at, e_at, c1_at, W, w, lane, tid, scale * sign,
-                         out + (long long)blockIdx.y * ldo + b * f.k, (long long)n_out - b * f.k, o);
+                         out + (long long)(vec0 + vi) * ldo + b * f.k, (long long)n_out - b * f.k, o);
+    }
 }
 
-template <typename VT, int H, int ENC, int NPASS>
+template <typename VT, int H, int ENC, int NPASS, bool MULTI>
 __global__ __launch_bounds__(1024, 4) void k_rsr_matvec1(
     const uint16_t *__restrict__ entries0, const uint16_t *__restrict__ codes0,
     const void *__restrict__ v, int C0, int n_in, int W, long long ldv,
@@ -631,12 +666,16 @@ __global__ __launch_bounds__(1024, 4) void k_rsr_matvec1(
         o.stamps[blockIdx.x * 16 + 13] = __builtin_amdgcn_s_getreg((20) | (0 << 6) | (31 << 11));  // XCC_ID
     }
 #endif
-    single_pass<VT, H, ENC, true>(entries0, codes0, wsign0, C0, sign0, v, ldv, n_in, W, f, o.out,
-                                  o.ldo, o.n_out, o.scale, o);
+    // MULTI (one-pass kinds only): the workgroup multiplies o.vper vectors one after the
+    // other, keeping the stream in registers; otherwise one vector per workgroup
+    const int vec0 = MULTI ? blockIdx.y * o.vper : blockIdx.y;
+    const int nvec = MULTI ? min(o.vper, o.batch - vec0) : 1;
+    single_pass<VT, H, ENC, true, MULTI>(entries0, codes0, wsign0, C0, sign0, v, ldv, n_in, W, f,
+                                         o.out, o.ldo, o.n_out, o.scale, o, vec0, nvec);
     if (NPASS == 2) {
         __syncthreads();
-        single_pass<VT, H, ENC, false>(a1.entries, a1.codes, a1.wsign, a1.C, a1.sign, v, ldv, n_in, W,
-                                       f, o.out, o.ldo, o.n_out, o.scale, o);
+        single_pass<VT, H, ENC, false, false>(a1.entries, a1.codes, a1.wsign, a1.C, a1.sign, v, ldv,
+                                              n_in, W, f, o.out, o.ldo, o.n_out, o.scale, o, vec0, 1);
     }
     RSR_STAMP(7);
 }
@@ -653,10 +692,10 @@ struct LaunchArgs {
     bool single;  // every pass has at most W chunks: one chunk per wave, no loops
 };
 
-template <typename VT, int H, int ENC, int NPASS>
+template <typename VT, int H, int ENC, int NPASS, bool MULTI>
 hipError_t launch_single(const LaunchArgs &x) {
     static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
-    auto kern = k_rsr_matvec1<VT, H, ENC, NPASS>;
+    auto kern = k_rsr_matvec1<VT, H, ENC, NPASS, MULTI>;
     if (x.lds > attr_bytes) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)x.lds);
@@ -669,15 +708,19 @@ hipError_t launch_single(const LaunchArgs &x) {
     a1.wsign = x.a1.wsign;
     a1.C = x.a1.C;
     a1.sign = x.a1.sign;
-    hipLaunchKernelGGL(kern, dim3((unsigned)x.nblocks, (unsigned)x.batch), dim3(x.W * 64), x.lds,
-                       x.stream, x.a0.entries, x.a0.codes, x.v, x.a0.C, x.n_in, x.W, x.ldv,
+    const int groups = MULTI ? (x.batch + x.o.vper - 1) / x.o.vper : x.batch;
+    hipLaunchKernelGGL(kern, dim3((unsigned)x.nblocks, (unsigned)groups),
+                       dim3(x.W * 64), x.lds, x.stream, x.a0.entries, x.a0.codes, x.v, x.a0.C, x.n_in, x.W, x.ldv,
                        x.a0.wsign, x.f, x.a0.sign, a1, x.o);
     return hipGetLastError();
 }
 
 template <typename VT, int H, int ENC, int NPASS>
 hipError_t launch(const LaunchArgs &x) {
-    if (x.single) return launch_single<VT, H, ENC, NPASS>(x);
+    if (x.single) {
+        if (NPASS == 1 && x.o.vper > 1) return launch_single<VT, H, ENC, 1, true>(x);
+        return launch_single<VT, H, ENC, NPASS, false>(x);
+    }
     static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
     auto kern = k_rsr_matvec<VT, H, ENC, NPASS>;
     if (x.lds > attr_bytes) {
@@ -686,8 +729,8 @@ hipError_t launch(const LaunchArgs &x) {
         if (e != hipSuccess) return e;
         attr_bytes = x.lds;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)x.nblocks, (unsigned)x.batch), dim3(x.W * 64), x.lds,
-                       x.stream, x.a0, x.v, x.ldv, x.n_in, x.W, x.f, x.a1, x.o);
+    hipLaunchKernelGGL(kern, dim3((unsigned)x.nblocks, (unsigned)x.batch),
+                       dim3(x.W * 64), x.lds, x.stream, x.a0, x.v, x.ldv, x.n_in, x.W, x.f, x.a1, x.o);
     return hipGetLastError();
 }
 
@@ -895,6 +938,17 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     x.o.ldo = ldo;
     x.o.n_out = (int)h->rows;
     x.o.scale = scale;
+    x.o.batch = batch;
+    // enough workgroups to fill the chip twice over first, then several vectors per workgroup
+    // (measured: keeping the stream in registers pays once there are that many workgroups)
+    {
+        static const int forced = [] {  // RSR_VPER overrides the choice (tuning only)
+            const char *e = std::getenv("RSR_VPER");
+            return e ? std::atoi(e) : 0;
+        }();
+        const long long per = forced > 0 ? forced : (long long)h->nb * batch / 1024;
+        x.o.vper = (int)(per < 1 ? 1 : per > batch ? batch : per);
+    }
     x.o.stamps = nullptr;
     x.o.stop_after = 0;
 #ifdef RSR_PHASE_TIMING

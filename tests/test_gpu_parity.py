@@ -149,6 +149,29 @@ def test_batch_and_strides():
         assert np.max(np.abs(got[i, :rows] - want)) <= _tol(vals[i], 2.0)
 
 
+@pytest.mark.parametrize("kind,bf16,pad,batch", [
+    (rsr.RSR_TERNARY_FUSED, True, 0, 5), (rsr.RSR_TERNARY_FUSED, True, 3, 7),
+    (rsr.RSR_BINARY, False, 0, 6), (rsr.RSR_BINARY, False, 1, 5),
+    (rsr.RSR_TERNARY_2PASS, True, 8, 5), (rsr.RSR_DENSE_TERNARY_P2, True, 0, 5),
+    (rsr.RSR_DENSE_TERNARY_P2, True, 5, 19), (rsr.RSR_DENSE_TERNARY_P2, False, 2, 6)])
+def test_batch_many_blocks(kind, bf16, pad, batch):
+    """Enough blocks that one workgroup takes several vectors in turn; aligned and
+    unaligned vector strides; integer-valued vectors, so every output is exact."""
+    rows, cols, k = 2100, 264, 2
+    M = _matrix(kind, rows, cols, 77)
+    h = rsr.rsr_preprocess(_dev(M), k, kind)
+    vi = np.stack([gen.integer_f32(cols, seed=900 + i) for i in range(batch)])
+    vbuf = torch.zeros((batch, cols + pad), dtype=torch.bfloat16 if bf16 else torch.float32, device=DEV)
+    vbuf[:, :cols] = _dev(vi).to(vbuf.dtype)
+    out = torch.full((batch, rows + 3), -5.0, dtype=torch.float32, device=DEV)
+    rsr.rsr_matvec_ex(h, vbuf[:, :cols], scale=3.0, out=out[:, :rows])
+    got = out.cpu().numpy()
+    assert np.all(got[:, rows:] == -5.0)
+    for i in range(batch):
+        want = oracle.dense_matvec(M, vi[i].astype(np.float64), 3.0)
+        assert np.array_equal(got[i, :rows].astype(np.float64), want), "vector %d" % i
+
+
 def test_second_stream():
     rows, cols = 64, 2048
     M = _matrix(rsr.RSR_BINARY, rows, cols, 41)
