@@ -44,6 +44,10 @@ def parse_args():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain device copy of 256 MiB (a kernel of known traffic, "
                          "to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--configs", action="store_true",
+                    help="instead of the metric line: time the other workload families (binary "
+                         "1024^2, ternary 4096^2 over k, the 2B and 8B layer sets, the retrieval "
+                         "table) warm and cold, RSR and dense, one JSON line with a list")
     return ap.parse_args()
 
 
@@ -74,6 +78,105 @@ def time_graph(torch, launch_fn, steps, warmup):
         return t0.elapsed_time(t1)
 
 
+def run_configs(args):
+    """The workload families beside the metric one.  A step = the whole layer sequence of a
+    family on one stream; cold = weight sets cycled so that > 600 MB of streams pass between
+    two uses of the same set (fewer sets when one set is that large already)."""
+    import numpy as np
+    import torch
+    import rsr_inputs as gen
+    import paper_2603_27462_amd as rsr
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    rsr.load_library()
+    B, T2, TF, D = (rsr.RSR_BINARY, rsr.RSR_TERNARY_2PASS, rsr.RSR_TERNARY_FUSED,
+                    rsr.RSR_DENSE_TERNARY_P2)
+    kind_name = {B: "binary", T2: "2pass", TF: "fused", D: "dense_packed2"}
+    steps = min(args.steps, 500)
+    results = []
+
+    def one(name, make_layers, k, kind, bf16, batch=1, max_sets=40):
+        """make_layers(set_index) -> list of int8 matrices (numpy)."""
+        vt = rsr.RSR_BF16 if bf16 else rsr.RSR_F32
+        try:
+            sets = [[rsr.rsr_preprocess(torch.from_numpy(M).to(dev), k, kind) for M in make_layers(0)]]
+        except rsr.RsrError as e:
+            results.append({"workload": name, "kind": kind_name[kind], "k": k, "error": str(e)})
+            return
+        nbytes = sum(rsr.rsr_algorithmic_bytes(h, vt, batch) for h in sets[0])
+        nsets = int(min(max_sets, max(2, np.ceil(COLD_WORKING_SET / nbytes))))
+        for i in range(1, nsets):
+            sets.append([rsr.rsr_preprocess(torch.from_numpy(M).to(dev), k, kind) for M in make_layers(i)])
+        vs, outs = [], []
+        for h in sets[0]:
+            shape = (batch, h.cols)
+            x = torch.randn(shape, device=dev)
+            vs.append(x.to(torch.bfloat16) if bf16 else x)
+            outs.append(torch.empty((nsets, batch, h.rows), dtype=torch.float32, device=dev))
+
+        def cold(i, s):
+            j = i % nsets
+            for h, v, o in zip(sets[j], vs, outs):
+                rsr.rsr_matvec_ex(h, v, out=o[j], stream=s)
+
+        def warm(i, s):
+            for h, v, o in zip(sets[0], vs, outs):
+                rsr.rsr_matvec_ex(h, v, out=o[0], stream=s)
+
+        tc = time_graph(torch, cold, steps, 50) * 1e3 / steps
+        tw = time_graph(torch, warm, steps, 50) * 1e3 / steps
+        results.append({"workload": name, "kind": kind_name[kind], "k": k, "batch": batch,
+                        "k_used": [h.k for h in sets[0]],
+                        "v_dtype": "bf16" if bf16 else "f32", "layers": len(sets[0]),
+                        "weight_sets": nsets, "algorithmic_MB": nbytes / 1e6,
+                        "cold_us": tc, "warm_us": tw, "cold_GBs": nbytes / tc / 1e3,
+                        "kernel": rsr.rsr_kernel_name(sets[0][0], vt)})
+        print("  %-44s %-13s k=%2d batch=%d: cold %8.2f us  warm %8.2f us  %6.1f MB  %5.0f GB/s  k used %s"
+              % (name, kind_name[kind], k, batch, tc, tw, nbytes / 1e6, nbytes / tc / 1e3,
+                 sorted(set(h.k for h in sets[0]))),
+              file=sys.stderr, flush=True)
+        for hs in sets:
+            for h in hs:
+                rsr.rsr_destroy(h)
+
+    s0 = gen.BASE_SEED
+    one("binary 1024x1024", lambda i: [gen.binary_matrix(1024, 1024, 0.5, s0 + 100 + i)], 8, B, False)
+    for k in (4, 6, 8, 10):
+        for kind in (T2, TF):
+            one("ternary 4096x4096", lambda i: [gen.ternary_matrix(4096, 4096, 1 / 3, s0 + 200 + i)],
+                k, kind, False)
+    one("ternary 4096x4096", lambda i: [gen.ternary_matrix(4096, 4096, 1 / 3, s0 + 200 + i)], 0, D, False)
+
+    def layers_2b(i):
+        return [gen.ternary_matrix(l.rows, l.cols, gen.LLM_2B_P_ZERO, s0 + 300 + 10 * i + n)
+                for n, l in enumerate(gen.LLM_2B_LAYERS)]
+
+    def layers_8b(i):
+        return [gen.ternary_matrix(l.rows, l.cols, gen.LLM_8B_P_ZERO, s0 + 700 + 10 * i + n)
+                for n, l in enumerate(gen.LLM_8B_LAYERS)]
+
+    def layers_2b_merged(i):
+        # layers that share their input (q, k, v; gate, up) stacked row-wise: one handle and
+        # one launch each, v staged once
+        m = layers_2b(i)
+        return [np.concatenate(m[0:3]), m[3], np.concatenate(m[4:6]), m[6]]
+
+    for k in (6, 8, 0):      # k = 0: the library picks k per layer by timing
+        one("2B layer set (7 layers)", layers_2b, k, TF, True)
+    one("2B layer set (7 layers)", layers_2b, 0, D, True)
+    one("2B layer set, siblings stacked (4 launches)", layers_2b_merged, 0, TF, True)
+    one("2B layer set, siblings stacked (4 launches)", layers_2b_merged, 0, D, True)
+    for batch in (1, 4):
+        for k in (8, 0):
+            one("8B layers (3)", layers_8b, k, TF, True, batch=batch, max_sets=12)
+        one("8B layers (3)", layers_8b, 0, D, True, batch=batch, max_sets=12)
+    table = lambda i: [gen.column_density_binary(1 << 20, 256, 0.05, 0.5, s0 + 900 + i)]
+    for k in (4, 8):
+        one("retrieval 1048576x256", table, k, B, False, max_sets=6)
+    one("retrieval 1048576x256", table, 0, D, False, max_sets=6)
+    print(json.dumps({"configs": results, "steps": steps, "data": "synthetic", "n_gpus": 1}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -89,6 +192,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.configs:
+        run_configs(args)
+        return
     dev = "cuda:0"
     torch.cuda.set_device(0)
     rsr.load_library()

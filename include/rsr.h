@@ -58,7 +58,11 @@ enum {
  *   rows  number of outputs (>= 1); need not be a multiple of k (the last
  *         block is completed with zero rows, whose outputs are never written)
  *   cols  length of v, 1 <= cols <= 32766
- *   k     block height.  RSR_BINARY / RSR_TERNARY_2PASS: 1..15;
+ *   k     block height, or 0 to let the library choose (paper, Conclusion: the best
+ *         k moves with the device and the matrix shape): it preprocesses with
+ *         k = 4, 6, 8, 10, 12 (4..8 for RSR_TERNARY_FUSED), times the multiply kernel of
+ *         each on this device with a bf16 vector and keeps the fastest;
+ *         rsr_block_height() tells the choice.  RSR_BINARY / RSR_TERNARY_2PASS: 1..15;
  *         RSR_TERNARY_FUSED: 1..10; in all cases 4*P + 4*(cols+1) + 9 KiB
  *         must fit the 160 KiB of LDS (P = 2^k or 3^k), else
  *         RSR_EUNSUPPORTED.  Ignored for RSR_DENSE_TERNARY_P2.
@@ -128,6 +132,7 @@ int rsr_get_offsets(rsr_handle_t h, int pass, uint32_t *host_off);
 int rsr_get_packed(rsr_handle_t h, uint8_t *host_packed);
 
 int64_t rsr_num_blocks(rsr_handle_t h);   /* nb = ceil(rows/k); 0 for the dense kind */
+int rsr_block_height(rsr_handle_t h);     /* k of the handle; 0 for the dense kind    */
 int64_t rsr_num_patterns(rsr_handle_t h); /* P per pass; 0 for the dense kind        */
 int rsr_num_passes(rsr_handle_t h);       /* 1 or 2; 0 for the dense kind            */
 

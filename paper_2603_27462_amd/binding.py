@@ -20,7 +20,8 @@ RSR_F32, RSR_BF16 = 0, 1
 exported_symbols = [
     "rsr_preprocess", "rsr_matvec", "rsr_matvec_ex", "rsr_destroy", "rsr_last_error",
     "rsr_error_string", "rsr_get_perm", "rsr_get_offsets", "rsr_get_packed",
-    "rsr_num_blocks", "rsr_num_patterns", "rsr_num_passes", "rsr_algorithmic_bytes",
+    "rsr_num_blocks", "rsr_block_height", "rsr_num_patterns", "rsr_num_passes",
+    "rsr_algorithmic_bytes",
     "rsr_kernel_name",
 ]
 
@@ -69,6 +70,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         getattr(lib, name).argtypes = [vp]
     lib.rsr_num_passes.restype = ci
     lib.rsr_num_passes.argtypes = [vp]
+    lib.rsr_block_height.restype = ci
+    lib.rsr_block_height.argtypes = [vp]
     lib.rsr_algorithmic_bytes.restype = i64
     lib.rsr_algorithmic_bytes.argtypes = [vp, ci, ci]
     lib.rsr_kernel_name.restype = ctypes.c_char_p
@@ -116,7 +119,7 @@ def rsr_preprocess(M, k: int, kind: int) -> Handle:
         ptr = load_library().rsr_preprocess(M.data_ptr(), rows, cols, int(k), int(kind))
     if not ptr:
         raise RsrError(rsr_last_error(), "rsr_preprocess")
-    return Handle(ptr, rows, cols, int(k), int(kind))
+    return Handle(ptr, rows, cols, int(load_library().rsr_block_height(ptr)), int(kind))
 
 
 def rsr_destroy(h: Handle) -> None:
@@ -171,6 +174,10 @@ def rsr_num_blocks(h: Handle) -> int:
 
 def rsr_num_patterns(h: Handle) -> int:
     return int(load_library().rsr_num_patterns(h.ptr))
+
+
+def rsr_block_height(h: Handle) -> int:
+    return int(load_library().rsr_block_height(h.ptr))
 
 
 def rsr_num_passes(h: Handle) -> int:

@@ -151,16 +151,10 @@ done:
 
 }  // namespace
 
-extern "C" {
+namespace {
 
-rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, int kind) {
-    if (!M || rows < 1 || cols < 1 || (!is_rsr_kind(kind) && kind != RSR_DENSE_TERNARY_P2)) {
-        fail(RSR_EINVAL);
-        return nullptr;
-    }
-    if (is_rsr_kind(kind) && k < 1) { fail(RSR_EINVAL); return nullptr; }
-    if (cols > rsr::kMaxCols || rows > (int64_t)1 << 30) { fail(RSR_EUNSUPPORTED); return nullptr; }
-
+// Preprocessing with a given block height (k is ignored for the dense kind).
+rsr_handle_s *preprocess_with_k(const int8_t *M, int64_t rows, int64_t cols, int k, int kind) {
     rsr_handle_s *h = new (std::nothrow) rsr_handle_s();
     if (!h) { fail(RSR_ENOMEM); return nullptr; }
     h->magic = rsr::kMagic;
@@ -198,6 +192,85 @@ rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, 
     g_last_error = RSR_OK;
     return h;
 }
+
+// Average duration in microseconds of the multiply kernel of h on a zero bf16 vector
+// (null stream, device buffers supplied by the caller); negative on failure.
+float time_matvec(rsr_handle_s *h, const void *v, float *out) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    float ms = -1.0f;
+    constexpr int kWarm = 3, kTimed = 10;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto done;
+    for (int i = 0; i < kWarm; ++i)
+        if (rsr::launch_rsr_matvec(h, v, RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) != hipSuccess) goto done;
+    if (hipEventRecord(e0, 0) != hipSuccess) goto done;
+    for (int i = 0; i < kTimed; ++i)
+        if (rsr::launch_rsr_matvec(h, v, RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) != hipSuccess) goto done;
+    if (hipEventRecord(e1, 0) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) goto done;
+    if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) ms = -1.0f;
+done:
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    return ms < 0.0f ? -1.0f : ms * 1e3f / kTimed;
+}
+
+// k = 0: the block height is a tuning knob whose best value moves with the shape and the
+// device (paper, Conclusion and the k sweep of its interface), so it is chosen by
+// measurement: preprocess with each candidate height, time the multiply kernel, keep
+// the fastest handle.
+rsr_handle_s *preprocess_auto_k(const int8_t *M, int64_t rows, int64_t cols, int kind) {
+    static const int fused_k[] = {4, 5, 6, 7, 8};
+    static const int binary_k[] = {4, 6, 8, 10, 12};
+    const int *cand = (kind == RSR_TERNARY_FUSED) ? fused_k : binary_k;
+    uint16_t *v = nullptr;
+    float *out = nullptr;
+    rsr_handle_s *best = nullptr;
+    float best_us = 0.0f;
+    int last_err = RSR_EUNSUPPORTED;
+    if (dev_alloc(&v, (size_t)cols) != hipSuccess || dev_alloc(&out, (size_t)rows) != hipSuccess ||
+        hipMemset(v, 0, (size_t)cols * 2) != hipSuccess) {
+        (void)hipGetLastError();
+        last_err = RSR_ENOMEM;
+    } else {
+        for (int i = 0; i < 5; ++i) {
+            rsr_handle_s *h = preprocess_with_k(M, rows, cols, cand[i], kind);
+            if (!h) {
+                if (g_last_error != RSR_EUNSUPPORTED) { last_err = g_last_error; break; }
+                continue;
+            }
+            const float us = time_matvec(h, v, out);
+            if (us >= 0.0f && (!best || us < best_us)) {
+                if (best) free_handle(best);
+                best = h;
+                best_us = us;
+            } else {
+                free_handle(h);
+            }
+        }
+        (void)hipDeviceSynchronize();
+    }
+    if (v) (void)hipFree(v);
+    if (out) (void)hipFree(out);
+    if (!best) { fail(last_err); return nullptr; }
+    g_last_error = RSR_OK;
+    return best;
+}
+
+}  // namespace
+
+extern "C" {
+
+rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, int kind) {
+    if (!M || rows < 1 || cols < 1 || (!is_rsr_kind(kind) && kind != RSR_DENSE_TERNARY_P2)) {
+        fail(RSR_EINVAL);
+        return nullptr;
+    }
+    if (is_rsr_kind(kind) && k < 0) { fail(RSR_EINVAL); return nullptr; }
+    if (cols > rsr::kMaxCols || rows > (int64_t)1 << 30) { fail(RSR_EUNSUPPORTED); return nullptr; }
+    if (is_rsr_kind(kind) && k == 0) return preprocess_auto_k(M, rows, cols, kind);
+    return preprocess_with_k(M, rows, cols, k, kind);
+}
+
+int rsr_block_height(rsr_handle_t h) { return good(h) ? h->k : 0; }
 
 int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void *out, int batch,
                   int64_t ldv, int64_t ldo, void *stream) {
@@ -315,7 +388,7 @@ const char *rsr_kernel_name(rsr_handle_t h, int v_dtype) {
         fail(RSR_EINVAL);
         return nullptr;
     }
-    return h->kind == RSR_DENSE_TERNARY_P2 ? rsr::dense_matvec_kernel_name(v_dtype)
+    return h->kind == RSR_DENSE_TERNARY_P2 ? rsr::dense_matvec_kernel_name(h, v_dtype)
                                            : rsr::rsr_matvec_kernel_name(v_dtype, h->H, h->enc, h->npass, rsr::matvec_is_single(h));
 }
 

@@ -124,15 +124,16 @@ __device__ __forceinline__ void tile_mfma(const u32x4 q, uint32_t vb, uint32_t p
     }
 }
 
-// Workgroup = 8 waves = one group of 16 rows times up to 16 vectors (the B columns of the
-// MFMA); the waves split the tiles of every slab.  LDS: vector n at n * vstride (planes
+// Workgroup = 8 waves = 8/wpg groups of 16 rows, times up to 16 vectors (the B columns of
+// the MFMA); the wpg waves of a row group split the tiles of every slab (wpg = 8 unless
+// the matrix has fewer than 8 column tiles).  LDS: vector n at n * vstride (planes
 // back to back; the stride is padded by 64 bytes so that the 16-byte reads of the 64
 // lanes -- 16 vectors x 4 column slices -- fall on distinct banks), then the partial
 // results, float [8 waves][16 vectors][16 rows].
-template <typename VT>
+template <typename VT, int wpg>
 __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
-    const u32x4 *__restrict__ tiled, int ntiles, int slab_tiles, int n_in, int n_out,
-    const void *__restrict__ v, long long ldv, int batch, int nv, float *__restrict__ out,
+    const u32x4 *__restrict__ tiled, int ntiles, int slab_tiles, int ngroups, int n_in,
+    int n_out, const void *__restrict__ v, long long ldv, int batch, int nv, float *__restrict__ out,
     long long ldo, float scale) {
     constexpr int PLANES = sizeof(VT) == 4 ? 3 : 1;
     constexpr int nthreads = kDenseWaves * 64;
@@ -143,7 +144,11 @@ __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
     const uint32_t plane = (uint32_t)slab_tiles * kDenseTileCols * 2u;
     const uint32_t vstride = plane * PLANES + 64u;
     const uint32_t red_at = vstride * (uint32_t)nv;
-    const u32x4 *wp = tiled + ((long long)blockIdx.x * ntiles) * 64 + lane;
+    constexpr int gpw = kDenseWaves / wpg;              // row groups of this workgroup
+    const int wg = w / wpg, ws = w - wg * wpg;          // the wave's row group and share
+    const long long G = (long long)blockIdx.x * gpw + wg;
+    const bool live = G < ngroups;
+    const u32x4 *wp = tiled + ((live ? G : 0) * ntiles) * 64 + lane;
     // B column lane%16 is vector lane%16 (columns without a vector repeat vector 0)
     const int col = lane & 15;
     const uint32_t lane_vb = (uint32_t)(col < nvh ? col : 0) * vstride + (uint32_t)(lane >> 4) * 16u;
@@ -152,7 +157,7 @@ __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
     for (int s0 = 0; s0 < ntiles; s0 += slab_tiles) {
         const int st = min(slab_tiles, ntiles - s0);  // tiles in this slab
         // this wave's tiles of the slab: [t0, t1)
-        const int t0 = s0 + (st * w) / kDenseWaves, t1 = s0 + (st * (w + 1)) / kDenseWaves;
+        const int t0 = s0 + (st * ws) / wpg, t1 = live ? s0 + (st * (ws + 1)) / wpg : t0;
         // the first eight weight loads leave before v is staged
         u32x4 q[8];
         if (t1 > t0) {
@@ -188,16 +193,39 @@ __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
         *lds_float(at + 12) = acc.w;
     }
     __syncthreads();
-    if (tid < kDenseRows * 16) {
-        const int n = tid >> 4, r = tid & 15;
+    for (int e = tid; e < gpw * 256; e += nthreads) {  // (row group, vector, row)
+        const int g = e >> 8, n = (e >> 4) & 15, r = e & 15;
         float sum = 0.0f;
 #pragma unroll
-        for (int i = 0; i < kDenseWaves; ++i)
-            sum += *lds_float(red_at + (uint32_t)((i * 16 + n) * 16 + r) * 4u);
-        const long long row = (long long)blockIdx.x * kDenseRows + r;
+        for (int i = 0; i < wpg; ++i)
+            sum += *lds_float(red_at + (uint32_t)(((g * wpg + i) * 16 + n) * 16 + r) * 4u);
+        const long long row = ((long long)blockIdx.x * gpw + g) * kDenseRows + r;
         // the weights were +-2
         if (n < nvh && row < n_out) out[(long long)(vec0 + n) * ldo + row] = (0.5f * scale) * sum;
     }
+}
+
+
+template <typename VT, int WPG>
+hipError_t launch_w(const rsr_handle_s *h, const void *v, float scale, float *out, int batch,
+                    int64_t ldv, int64_t ldo, hipStream_t stream, int nv, int slab_tiles, size_t lds) {
+    static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
+    auto kern = k_dense_matvec<VT, WPG>;
+    const int ntiles = (int)(h->row_bytes / (kDenseTileCols / 4));
+    const int ngroups = (int)((h->rows + kDenseRows - 1) / kDenseRows);
+    if (lds > attr_bytes) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_bytes = lds;
+    }
+    constexpr int gpw = kDenseWaves / WPG;
+    hipLaunchKernelGGL(kern, dim3((unsigned)((ngroups + gpw - 1) / gpw), (unsigned)((batch + nv - 1) / nv)),
+                       dim3(kDenseWaves * 64), lds, stream,
+                       reinterpret_cast<const u32x4 *>(h->packed), ntiles, slab_tiles, ngroups,
+                       (int)h->cols, (int)h->rows, v, (long long)ldv, batch, nv, out, (long long)ldo,
+                       scale);
+    return hipGetLastError();
 }
 
 constexpr size_t kDenseLdsBudget = 150 * 1024;
@@ -205,10 +233,7 @@ constexpr size_t kDenseLdsBudget = 150 * 1024;
 template <typename VT>
 hipError_t launch(const rsr_handle_s *h, const void *v, float scale, float *out, int batch,
                   int64_t ldv, int64_t ldo, hipStream_t stream) {
-    static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
-    auto kern = k_dense_matvec<VT>;
     const int ntiles = (int)(h->row_bytes / (kDenseTileCols / 4));
-    const int ngroups = (int)((h->rows + kDenseRows - 1) / kDenseRows);
     const int planes = sizeof(VT) == 4 ? 3 : 1;
     // vectors per workgroup (the weights are read once for all of them) and the slab of
     // columns staged at a time: as many vectors as keep a slab of at least 8 tiles in LDS
@@ -224,17 +249,11 @@ hipError_t launch(const rsr_handle_s *h, const void *v, float scale, float *out,
     if (slab_tiles < 1) slab_tiles = 1;
     const size_t lds = (size_t)nv * ((size_t)slab_tiles * kDenseTileCols * 2 * planes + 64) +
                        (size_t)kDenseWaves * 16 * 16 * 4;
-    if (lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_bytes = lds;
-    }
-    hipLaunchKernelGGL(kern, dim3((unsigned)ngroups, (unsigned)((batch + nv - 1) / nv)),
-                       dim3(kDenseWaves * 64), lds, stream,
-                       reinterpret_cast<const u32x4 *>(h->packed), ntiles, slab_tiles, (int)h->cols,
-                       (int)h->rows, v, (long long)ldv, batch, nv, out, (long long)ldo, scale);
-    return hipGetLastError();
+    // waves per row group: a power of two, at most one per tile of a slab
+    if (slab_tiles >= 8) return launch_w<VT, 8>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
+    if (slab_tiles >= 4) return launch_w<VT, 4>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
+    if (slab_tiles >= 2) return launch_w<VT, 2>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
+    return launch_w<VT, 1>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
 }
 
 }  // namespace
@@ -256,8 +275,14 @@ hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype
                                  : launch<float>(h, v, scale, out, batch, ldv, ldo, stream);
 }
 
-const char *dense_matvec_kernel_name(int v_dtype) {
-    return v_dtype == RSR_BF16 ? "k_dense_matvec<unsigned short>" : "k_dense_matvec<float>";
+const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype) {
+    // the instantiation a single vector launches
+    const int64_t ntiles = h->row_bytes / (kDenseTileCols / 4);
+    const bool bf = v_dtype == RSR_BF16;
+    if (ntiles >= 8) return bf ? "k_dense_matvec<unsigned short, 8>" : "k_dense_matvec<float, 8>";
+    if (ntiles >= 4) return bf ? "k_dense_matvec<unsigned short, 4>" : "k_dense_matvec<float, 4>";
+    if (ntiles >= 2) return bf ? "k_dense_matvec<unsigned short, 2>" : "k_dense_matvec<float, 2>";
+    return bf ? "k_dense_matvec<unsigned short, 1>" : "k_dense_matvec<float, 1>";
 }
 
 }  // namespace rsr

@@ -96,7 +96,7 @@ hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype
 const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass, bool single);
 // True when every pass has at most W chunks per block (one chunk per wave, no loops).
 bool matvec_is_single(const rsr_handle_s *h);
-const char *dense_matvec_kernel_name(int v_dtype);
+const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype);
 
 // Picks the chunk size (H loads of 512 entries per wave) and the number of
 // waves per workgroup for blocks whose longest stream has `longest` entries.

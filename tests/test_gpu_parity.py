@@ -196,6 +196,21 @@ def test_dense_packed_parity(rows, cols):
 
 
 # ------------------------------------------------------------------- error behaviour
+@pytest.mark.parametrize("kind,rows,cols", [(rsr.RSR_TERNARY_FUSED, 320, 1024),
+                                            (rsr.RSR_BINARY, 257, 700),
+                                            (rsr.RSR_TERNARY_2PASS, 96, 2048)])
+def test_library_chosen_block_height(kind, rows, cols):
+    """k = 0: the library picks the height by timing; whatever it picks, the artifacts are
+    the oracle's for that k and the product is the dense one."""
+    M = _matrix(kind, rows, cols, 123)
+    h = rsr.rsr_preprocess(_dev(M), 0, kind)
+    k = rsr.rsr_block_height(h)
+    assert k in ((4, 5, 6, 7, 8) if kind == rsr.RSR_TERNARY_FUSED else (4, 6, 8, 10, 12))
+    assert h.k == k and rsr.rsr_num_blocks(h) == -(-rows // k)
+    _check_artifacts(h, oracle.preprocess(M, k, KINDS[kind]))
+    _check_matvec(h, M, cols, 17)
+
+
 def test_errors():
     M = _dev(gen.ternary_matrix(16, 64, 0.3, 1))
     with pytest.raises(rsr.RsrError) as e:
@@ -208,7 +223,7 @@ def test_errors():
         rsr.rsr_preprocess(M, 10, rsr.RSR_TERNARY_FUSED)  # 3^10 bins do not fit LDS
     assert e.value.code == 3
     with pytest.raises(rsr.RsrError) as e:
-        rsr.rsr_preprocess(M, 0, rsr.RSR_TERNARY_2PASS)
+        rsr.rsr_preprocess(M, -2, rsr.RSR_TERNARY_2PASS)
     assert e.value.code == 1
     with pytest.raises(rsr.RsrError) as e:
         rsr.rsr_preprocess(M, 4, 9)
