@@ -9,6 +9,8 @@
 //                the compact stream the multiply kernel reads: 16-bit entries,
 //                zero-contribution group dropped, one tail flag per group,
 //                laid out for coalesced per-lane strips
+#include <cstdlib>
+
 #include "rsr_internal.h"
 
 namespace rsr {
@@ -208,6 +210,65 @@ __global__ __launch_bounds__(kThreads) void k_pack_stream(const uint16_t *__rest
     }
 }
 
+// Reorders the logical stream inside its groups so that the LDS gathers of the multiply
+// kernel collide less.  Gather instruction i of a wave reads entry i of all 64 strips of a
+// chunk; the LDS serves the two half-waves side by side and needs one cycle per distinct
+// dword that falls on the same of its 32 banks.  The order of the columns inside a group
+// is free for the kernel (sums commute up to rounding; the canonical pi is not touched),
+// so for every run of entries of one group inside a strip, each slot takes the remaining
+// column whose bank (for a bf16 vector: (col / 2) mod 32) is least loaded so far in that
+// slot of the half-wave; two more sweeps re-place every strip against all the others.
+// One wave per (block, chunk): thread = (half-wave, slot), strips in order; the first slot
+// of a run places the run.
+constexpr int kSpreadSweeps = 3;
+
+__global__ __launch_bounds__(64) void k_spread_banks(uint16_t *__restrict__ logical, int64_t nb,
+                                                     int64_t C, int H) {
+    __shared__ uint8_t load[2][32][33];  // [half][slot][bank], padded
+    __shared__ uint16_t buf[2][32];      // the strip being placed: column per slot
+    const int epl = 8 * H;
+    const int half = threadIdx.x >> 5, slot = threadIdx.x & 31;
+    const bool live = slot < epl;
+    for (int64_t chunk = blockIdx.x; chunk < nb * C; chunk += gridDim.x) {
+        uint16_t *cb = logical + chunk * 64 * epl;
+        for (int k = 0; k < 33; ++k) load[half][slot][k] = 0;
+        __syncthreads();
+        for (int sweep = 0; sweep < kSpreadSweeps; ++sweep) {
+            for (int l = 0; l < 32; ++l) {
+                uint16_t *st = cb + (32 * half + l) * epl;
+                const uint32_t entry = live ? st[slot] : 1u;  // slots past the strip: tails, never run starts' business
+                const uint32_t tail = entry & 1u;
+                const uint64_t ball = __ballot(tail != 0);
+                const uint32_t tails = (uint32_t)(ball >> (32 * half));
+                buf[half][slot] = (uint16_t)(entry >> 1);
+                if (sweep > 0 && live) --load[half][slot][(entry >> 2) & 31];
+                __syncthreads();
+                const bool start = live && (slot == 0 || ((tails >> (slot - 1)) & 1u));
+                if (start) {
+                    const uint32_t rest = tails >> slot;
+                    int e = rest ? slot + __builtin_ctz(rest) : epl - 1;
+                    if (e > epl - 1) e = epl - 1;
+                    for (int sl = slot; sl <= e; ++sl) {
+                        int best = sl;
+                        uint8_t bl = load[half][sl][(buf[half][sl] >> 1) & 31];
+                        for (int t = sl + 1; t <= e; ++t) {
+                            const uint8_t x = load[half][sl][(buf[half][t] >> 1) & 31];
+                            if (x < bl) { bl = x; best = t; }
+                        }
+                        const uint16_t c = buf[half][best];
+                        buf[half][best] = buf[half][sl];
+                        buf[half][sl] = c;
+                        ++load[half][sl][(c >> 1) & 31];
+                    }
+                }
+                __syncthreads();
+                if (live) st[slot] = (uint16_t)((buf[half][slot] << 1) | tail);
+                __syncthreads();
+            }
+        }
+    }
+}
+
 // Final layout of the stream (see PassData): re-encodes the entries, moves
 // them to the lane-major slabs, and records for every lane strip the group
 // code of the first tail at or after its start (1 + tails before it).  Also
@@ -299,6 +360,15 @@ hipError_t launch_pack_stream(const uint16_t *pi, const uint32_t *off, int64_t n
                        (int)cols, P, S, scratch);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    {
+        static const bool off = std::getenv("RSR_NO_SPREAD") != nullptr;  // tuning only
+        const int64_t units = nb * C;
+        if (!off)
+            hipLaunchKernelGGL(k_spread_banks, dim3((unsigned)(units < 65536 ? units : 65536)), dim3(64),
+                               0, 0, scratch, nb, C, H);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     hipLaunchKernelGGL(k_finalize_stream, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, scratch,
                        nb, P, C, H, enc, entries, codes, err_flag);
     return hipGetLastError();
