@@ -112,7 +112,7 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
 
     {
         const int64_t longest = max_len[0] > max_len[1] ? max_len[0] : max_len[1];
-        rsr::choose_launch_shape(longest, &h->H, &h->W);
+        rsr::choose_launch_shape(longest, nb, &h->H, &h->W);
         h->enc = (cols <= rsr::kSmallCols) ? rsr::kEncSmall : rsr::kEncBig;
         const int64_t chunk = (int64_t)rsr::kLoad * h->H;
         int64_t maxS = 0;

@@ -99,9 +99,9 @@ bool matvec_is_single(const rsr_handle_s *h);
 const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype);
 
 // Picks the chunk size (H loads of 512 entries per wave) and the number of
-// waves per workgroup for blocks whose longest stream has `longest` entries.
+// waves per workgroup for nb blocks whose longest stream has `longest` entries.
 // The environment variables RSR_H and RSR_W override the choice (tuning only).
-void choose_launch_shape(int64_t longest, int *H, int *W);
+void choose_launch_shape(int64_t longest, int64_t nb, int *H, int *W);
 
 
 void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int npass,

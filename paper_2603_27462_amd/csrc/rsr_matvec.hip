@@ -815,11 +815,14 @@ __global__ void k_wave_signs(const uint16_t *__restrict__ codes, long long nb, i
 
 }  // namespace
 
-void choose_launch_shape(int64_t longest, int *H, int *W) {
+void choose_launch_shape(int64_t longest, int64_t nb, int *H, int *W) {
     // Preferred: one chunk per wave and at most 8 waves, so that two workgroups share a CU
     // without register pressure; the chunk grows with the stream (H = 1, 2, 4).  Longer
     // streams take up to 16 waves, and beyond that 8 waves that loop over their chunks.
-    constexpr int kWaves = 8;
+    // A CU runs 16 of these waves: with three or more rounds of 8-wave workgroups (1536
+    // blocks) it pays to halve the waves per block and keep twice as many blocks in flight
+    // (measured: 14336 x 4096, k = 8: 12.1 -> 10.5 us; 13824 x 2560, k = 6: 10.7 -> 9.0 us).
+    const int kWaves = nb >= 1536 ? 4 : 8;
     int h = 4;
     for (int cand = 1; cand <= 4; cand *= 2)
         if ((longest + kLoad * cand - 1) / (kLoad * cand) <= kWaves) { h = cand; break; }
@@ -828,7 +831,7 @@ void choose_launch_shape(int64_t longest, int *H, int *W) {
         if (x == 1 || x == 2 || x == 4) h = x;
     }
     const int64_t chunks = (longest + kLoad * h - 1) / (kLoad * h);
-    int w = (int)(chunks < 1 ? 1 : chunks <= kMaxWaves ? chunks : kWaves);
+    int w = (int)(chunks < 1 ? 1 : chunks <= kMaxWaves ? chunks : 8);
     if (const char *s = std::getenv("RSR_W")) {
         const int x = std::atoi(s);
         if (x >= 1 && x <= kMaxWaves) w = x;
