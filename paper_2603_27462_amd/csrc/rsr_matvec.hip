@@ -968,13 +968,13 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
 
 const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass, bool single) {
     // one static string per instantiation, as a profiler prints the template arguments
-    static char names[2][2][3][2][2][48];
+    static char names[2][2][3][2][2][64];
     const int hi = (H == 1) ? 0 : (H == 2) ? 1 : 2;
     char *n = names[single][v_dtype == RSR_BF16][hi][enc == kEncBig][npass == 2];
     if (!n[0])
-        std::snprintf(n, sizeof(names[0][0][0][0][0]), "k_rsr_matvec%s<%s, %d, %d, %d>",
+        std::snprintf(n, sizeof(names[0][0][0][0][0]), "k_rsr_matvec%s<%s, %d, %d, %d%s>",
                       single ? "1" : "", v_dtype == RSR_BF16 ? "unsigned short" : "float", H, enc,
-                      npass);
+                      npass, single ? ", false" : "");  // one vector per workgroup
     return n;
 }
 

@@ -221,51 +221,61 @@ __global__ __launch_bounds__(kThreads) void k_pack_stream(const uint16_t *__rest
 // One wave per (block, chunk): thread = (half-wave, slot), strips in order; the first slot
 // of a run places the run.
 constexpr int kSpreadSweeps = 3;
+constexpr int kSpreadMaxRun = 8;
 
 __global__ __launch_bounds__(64) void k_spread_banks(uint16_t *__restrict__ logical, int64_t nb,
                                                      int64_t C, int H) {
-    __shared__ uint8_t load[2][32][33];  // [half][slot][bank], padded
-    __shared__ uint16_t buf[2][32];      // the strip being placed: column per slot
+    __shared__ uint8_t load[2][32][33];   // [half][slot][bank], padded
+    __shared__ uint16_t strip[64][33];    // the chunk: [strip][slot], padded
     const int epl = 8 * H;
     const int half = threadIdx.x >> 5, slot = threadIdx.x & 31;
     const bool live = slot < epl;
     for (int64_t chunk = blockIdx.x; chunk < nb * C; chunk += gridDim.x) {
         uint16_t *cb = logical + chunk * 64 * epl;
+        for (int i = threadIdx.x; i < 64 * epl; i += 64) strip[i / epl][i % epl] = cb[i];
         for (int k = 0; k < 33; ++k) load[half][slot][k] = 0;
         __syncthreads();
         for (int sweep = 0; sweep < kSpreadSweeps; ++sweep) {
             for (int l = 0; l < 32; ++l) {
-                uint16_t *st = cb + (32 * half + l) * epl;
-                const uint32_t entry = live ? st[slot] : 1u;  // slots past the strip: tails, never run starts' business
+                uint16_t *st = strip[32 * half + l];
+                // slots past the strip count as tails, so that no run reaches into them
+                const uint32_t entry = live ? st[slot] : 1u;
                 const uint32_t tail = entry & 1u;
                 const uint64_t ball = __ballot(tail != 0);
                 const uint32_t tails = (uint32_t)(ball >> (32 * half));
-                buf[half][slot] = (uint16_t)(entry >> 1);
-                if (sweep > 0 && live) --load[half][slot][(entry >> 2) & 31];
+                if (live) {
+                    st[slot] = (uint16_t)(entry >> 1);  // columns only while the strip is placed
+                    if (sweep > 0) --load[half][slot][(entry >> 2) & 31];
+                }
                 __syncthreads();
                 const bool start = live && (slot == 0 || ((tails >> (slot - 1)) & 1u));
                 if (start) {
                     const uint32_t rest = tails >> slot;
                     int e = rest ? slot + __builtin_ctz(rest) : epl - 1;
                     if (e > epl - 1) e = epl - 1;
+                    // (long runs -- filler behind the last group, or one very common pattern --
+                    // are counted as they stand: placing them would cost run^2 steps)
+                    const bool place = e - slot < kSpreadMaxRun;
                     for (int sl = slot; sl <= e; ++sl) {
                         int best = sl;
-                        uint8_t bl = load[half][sl][(buf[half][sl] >> 1) & 31];
-                        for (int t = sl + 1; t <= e; ++t) {
-                            const uint8_t x = load[half][sl][(buf[half][t] >> 1) & 31];
+                        uint8_t bl = load[half][sl][(st[sl] >> 1) & 31];
+                        for (int t = sl + 1; place && t <= e; ++t) {
+                            const uint8_t x = load[half][sl][(st[t] >> 1) & 31];
                             if (x < bl) { bl = x; best = t; }
                         }
-                        const uint16_t c = buf[half][best];
-                        buf[half][best] = buf[half][sl];
-                        buf[half][sl] = c;
+                        const uint16_t c = st[best];
+                        st[best] = st[sl];
+                        st[sl] = c;
                         ++load[half][sl][(c >> 1) & 31];
                     }
                 }
                 __syncthreads();
-                if (live) st[slot] = (uint16_t)((buf[half][slot] << 1) | tail);
-                __syncthreads();
+                if (live) st[slot] = (uint16_t)((st[slot] << 1) | tail);
             }
         }
+        __syncthreads();
+        for (int i = threadIdx.x; i < 64 * epl; i += 64) cb[i] = strip[i / epl][i % epl];
+        __syncthreads();
     }
 }
 
