@@ -284,7 +284,7 @@ template <typename VT, int H, int ENC, bool FIRST>
 __device__ __forceinline__ void run_pass(const PassArgs &a, const void *v, long long ldv, int n_in,
                                          int W, const FoldArgs &f, const OutArgs &o, int vec) {
     constexpr int PF = 4 / H;  // chunks requested together (16 dwords per lane)
-    // LDS (byte addresses): v (n_in + zero slot) | wave-total terms | E[P] | red[k][fold threads]
+    // LDS (byte addresses): v (n_in + zero slot) | wave-total terms | E[P] | Tc zeros | C1[threads]
     const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
     const uint32_t corr_at = vbytes;          // float [16 waves][16 rows]
     const uint32_t e_at = vbytes + kLdsMisc;  // float [P]
@@ -453,9 +453,9 @@ __global__ __launch_bounds__(1024) void k_rsr_matvec(const PassArgs a0, const vo
 
 // ---- one chunk per wave ---------------------------------------------------------------
 // The common shape: the block's stream has at most W chunks, wave w owns chunk w, and
-// nothing loops.  Same phases as run_pass; the scatter phase takes its per-thread
-// constants (weights, first entry and count of the stage-1 share, stage-2 entry) from one
-// 32-byte record per fold thread.
+// nothing loops.  Same phases as run_pass, with every load of the pass requested up front
+// and the scatter-phase constants prepared while they are in flight.  MULTI: the workgroup
+// multiplies several vectors in turn with the stream kept in registers.
 struct SecondPass {
     const uint16_t *entries;
     const uint16_t *codes;
