@@ -174,6 +174,9 @@ def run_configs(args):
     for k in (4, 8):
         one("retrieval 1048576x256", table, k, B, False, max_sets=6)
     one("retrieval 1048576x256", table, 0, D, False, max_sets=6)
+    # 64 queries: back to back (the timed loop above is exactly that, per query) or one call
+    one("retrieval 1048576x256, 64 queries in one call", table, 8, B, False, batch=64, max_sets=2)
+    one("retrieval 1048576x256, 64 queries in one call", table, 0, D, False, batch=64, max_sets=2)
     print(json.dumps({"configs": results, "steps": steps, "data": "synthetic", "n_gpus": 1}))
 
 

@@ -107,6 +107,32 @@ int rsr_matvec(rsr_handle_t h, const void *v, void *out, void *stream);
 int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void *out,
                   int batch, int64_t ldv, int64_t ldo, void *stream);
 
+/*
+ * rsr_preprocess_transposed -- the handle of the transposed matrix: the product it serves is
+ * out[cols] = M^T * v[rows], i.e. the row vector v^T M that the paper's footnote on the
+ * original RSR formulation multiplies.  M as for rsr_preprocess (DEVICE int8 [rows][cols]);
+ * here rows <= 32766 (they become the inputs).  Transposes on the GPU, then preprocesses.
+ */
+rsr_handle_t rsr_preprocess_transposed(const int8_t *M, int64_t rows, int64_t cols, int k, int kind);
+
+/*
+ * Artifact reuse (paper, System Overview: the matrices are fixed, preprocessing is one-time
+ * and its result is kept): a handle as a flat byte string and back.
+ *
+ *   rsr_serialized_size  bytes rsr_serialize writes for h (-1 on a bad handle)
+ *   rsr_serialize        copies the handle to the HOST buffer host_buf of `capacity` bytes
+ *                        (RSR_EINVAL when too small); synchronous
+ *   rsr_deserialize      a new handle on the current device from `size` HOST bytes written by
+ *                        rsr_serialize of this library version.  The header is checked against
+ *                        every limit rsr_preprocess enforces and against the sizes it implies
+ *                        (RSR_EINVAL otherwise); the stream contents are taken as they are, so
+ *                        a damaged stream yields wrong products, never an out-of-range access
+ *                        to device memory (stream entries only ever address LDS).
+ */
+int64_t rsr_serialized_size(rsr_handle_t h);
+int rsr_serialize(rsr_handle_t h, void *host_buf, int64_t capacity);
+rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size);
+
 /* Frees the handle and its device buffers.  NULL is allowed. */
 void rsr_destroy(rsr_handle_t h);
 

@@ -20,6 +20,7 @@ RSR_F32, RSR_BF16 = 0, 1
 exported_symbols = [
     "rsr_preprocess", "rsr_matvec", "rsr_matvec_ex", "rsr_destroy", "rsr_last_error",
     "rsr_error_string", "rsr_get_perm", "rsr_get_offsets", "rsr_get_packed",
+    "rsr_preprocess_transposed", "rsr_serialized_size", "rsr_serialize", "rsr_deserialize",
     "rsr_num_blocks", "rsr_block_height", "rsr_num_patterns", "rsr_num_passes",
     "rsr_algorithmic_bytes",
     "rsr_kernel_name",
@@ -70,6 +71,14 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
         getattr(lib, name).argtypes = [vp]
     lib.rsr_num_passes.restype = ci
     lib.rsr_num_passes.argtypes = [vp]
+    lib.rsr_preprocess_transposed.restype = vp
+    lib.rsr_preprocess_transposed.argtypes = [vp, i64, i64, ci, ci]
+    lib.rsr_serialized_size.restype = i64
+    lib.rsr_serialized_size.argtypes = [vp]
+    lib.rsr_serialize.restype = ci
+    lib.rsr_serialize.argtypes = [vp, vp, i64]
+    lib.rsr_deserialize.restype = vp
+    lib.rsr_deserialize.argtypes = [vp, i64]
     lib.rsr_block_height.restype = ci
     lib.rsr_block_height.argtypes = [vp]
     lib.rsr_algorithmic_bytes.restype = i64
@@ -120,6 +129,48 @@ def rsr_preprocess(M, k: int, kind: int) -> Handle:
     if not ptr:
         raise RsrError(rsr_last_error(), "rsr_preprocess")
     return Handle(ptr, rows, cols, int(load_library().rsr_block_height(ptr)), int(kind))
+
+
+def rsr_preprocess_transposed(M, k: int, kind: int) -> Handle:
+    """Handle of M^T (M: int8 CUDA tensor [rows][cols]): multiplies vectors of length rows."""
+    import torch
+    if not (isinstance(M, torch.Tensor) and M.is_cuda and M.dtype == torch.int8 and M.dim() == 2):
+        raise TypeError("M must be a 2-D int8 CUDA tensor")
+    M = M.contiguous()
+    rows, cols = M.shape
+    with torch.cuda.device(M.device):
+        torch.cuda.current_stream().synchronize()
+        ptr = load_library().rsr_preprocess_transposed(M.data_ptr(), rows, cols, int(k), int(kind))
+    if not ptr:
+        raise RsrError(rsr_last_error(), "rsr_preprocess_transposed")
+    return Handle(ptr, cols, rows, int(load_library().rsr_block_height(ptr)), int(kind))
+
+
+def rsr_serialize(h: Handle) -> np.ndarray:
+    """The handle as a uint8 array (host)."""
+    lib = load_library()
+    n = int(lib.rsr_serialized_size(h.ptr))
+    if n < 0:
+        raise RsrError(rsr_last_error(), "rsr_serialized_size")
+    buf = np.empty(n, dtype=np.uint8)
+    rc = lib.rsr_serialize(h.ptr, buf.ctypes.data, n)
+    if rc:
+        raise RsrError(rc, "rsr_serialize")
+    return buf
+
+
+def rsr_deserialize(buf) -> Handle:
+    """A new handle on the current device from the bytes rsr_serialize returned."""
+    buf = np.ascontiguousarray(np.frombuffer(buf, dtype=np.uint8) if not isinstance(buf, np.ndarray) else buf,
+                               dtype=np.uint8)
+    lib = load_library()
+    ptr = lib.rsr_deserialize(buf.ctypes.data, buf.size)
+    if not ptr:
+        raise RsrError(rsr_last_error(), "rsr_deserialize")
+    # geometry from the header: kind, k at int32 words 2 and 3; rows, cols at bytes 40 and 48
+    words = buf[:64].view(np.int32)
+    rows, cols = (int(x) for x in buf[40:56].view(np.int64))
+    return Handle(ptr, rows, cols, int(lib.rsr_block_height(ptr)), int(words[2]))
 
 
 def rsr_destroy(h: Handle) -> None:

@@ -1,6 +1,7 @@
 // C ABI of librsr: argument checks, device-memory ownership, and the order of
 // the preprocessing launches.  All arithmetic of the method is in the kernels
 // (rsr_preprocess.hip, rsr_matvec.hip, rsr_dense.hip).
+#include <cstring>
 #include <new>
 #include <vector>
 
@@ -270,7 +271,173 @@ rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, 
     return preprocess_with_k(M, rows, cols, k, kind);
 }
 
+rsr_handle_t rsr_preprocess_transposed(const int8_t *M, int64_t rows, int64_t cols, int k, int kind) {
+    if (!M || rows < 1 || cols < 1) { fail(RSR_EINVAL); return nullptr; }
+    if (rows > rsr::kMaxCols || cols > (int64_t)1 << 30) { fail(RSR_EUNSUPPORTED); return nullptr; }
+    int8_t *T = nullptr;
+    if (dev_alloc(&T, (size_t)(rows * cols)) != hipSuccess) {
+        (void)hipGetLastError();
+        fail(RSR_ENOMEM);
+        return nullptr;
+    }
+    rsr_handle_t h = nullptr;
+    if (rsr::launch_transpose(M, rows, cols, T) != hipSuccess) {
+        (void)hipGetLastError();
+        fail(RSR_EHIP);
+    } else {
+        h = rsr_preprocess(T, cols, rows, k, kind);  // synchronises before returning
+    }
+    (void)hipFree(T);
+    return h;
+}
+
 int rsr_block_height(rsr_handle_t h) { return good(h) ? h->k : 0; }
+
+// ---- a handle as bytes --------------------------------------------------------------------
+}  // extern "C"
+
+namespace {
+
+constexpr uint32_t kSerialMagic = 0x53525352u;  // "RSRS"
+constexpr uint32_t kSerialVersion = 1;
+
+struct SerialHeader {
+    uint32_t magic, version;
+    int32_t kind, k, base, npass, W, H, enc, reserved;
+    int64_t rows, cols, nb, P, row_bytes;
+    int64_t C[2];
+    float sign[2];
+    int64_t total_bytes;  // header + buffers
+};
+
+struct Piece {
+    void **dev;      // the handle's device pointer
+    size_t bytes;
+};
+
+// The device buffers of a handle in file order, with the sizes its geometry dictates.
+std::vector<Piece> pieces_of(rsr_handle_s *h) {
+    std::vector<Piece> p;
+    if (h->kind == RSR_DENSE_TERNARY_P2) {
+        const size_t groups = (size_t)((h->rows + rsr::kDenseRows - 1) / rsr::kDenseRows);
+        p.push_back({reinterpret_cast<void **>(&h->packed), groups * rsr::kDenseRows * (size_t)h->row_bytes});
+        return p;
+    }
+    for (int ps = 0; ps < h->npass; ++ps) {
+        rsr::PassData &pd = h->pass[ps];
+        p.push_back({reinterpret_cast<void **>(&pd.pi), (size_t)(h->nb * h->cols) * 2});
+        p.push_back({reinterpret_cast<void **>(&pd.off), (size_t)(h->nb * (h->P + 1)) * 4});
+        p.push_back({reinterpret_cast<void **>(&pd.entries), (size_t)(h->nb * pd.C * rsr::kLoad * h->H) * 2});
+        p.push_back({reinterpret_cast<void **>(&pd.codes), (size_t)(h->nb * pd.C * 64) * 2});
+        p.push_back({reinterpret_cast<void **>(&pd.wsign), (size_t)(h->nb * h->W * 16)});
+    }
+    p.push_back({reinterpret_cast<void **>(&h->fpack), (size_t)h->k * h->fold.G * 64 * 4});
+    p.push_back({reinterpret_cast<void **>(&h->fshare), (size_t)h->W * 64 * 4});
+    return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t rsr_serialized_size(rsr_handle_t h) {
+    if (!good(h)) { fail(RSR_EINVAL); return -1; }
+    int64_t total = (int64_t)sizeof(SerialHeader);
+    for (const Piece &pc : pieces_of(h)) total += (int64_t)pc.bytes;
+    return total;
+}
+
+int rsr_serialize(rsr_handle_t h, void *host_buf, int64_t capacity) {
+    if (!good(h) || !host_buf) return fail(RSR_EINVAL);
+    const int64_t total = rsr_serialized_size(h);
+    if (capacity < total) return fail(RSR_EINVAL);
+    SerialHeader hd;
+    std::memset(&hd, 0, sizeof(hd));
+    hd.magic = kSerialMagic;
+    hd.version = kSerialVersion;
+    hd.kind = h->kind; hd.k = h->k; hd.base = h->base; hd.npass = h->npass;
+    hd.W = h->W; hd.H = h->H; hd.enc = h->enc;
+    hd.rows = h->rows; hd.cols = h->cols; hd.nb = h->nb; hd.P = h->P; hd.row_bytes = h->row_bytes;
+    for (int ps = 0; ps < 2; ++ps) { hd.C[ps] = h->pass[ps].C; hd.sign[ps] = h->pass[ps].sign; }
+    hd.total_bytes = total;
+    unsigned char *out = static_cast<unsigned char *>(host_buf);
+    std::memcpy(out, &hd, sizeof(hd));
+    size_t at = sizeof(hd);
+    for (const Piece &pc : pieces_of(h)) {
+        if (hipMemcpy(out + at, *pc.dev, pc.bytes, hipMemcpyDeviceToHost) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(RSR_EHIP);
+        }
+        at += pc.bytes;
+    }
+    g_last_error = RSR_OK;
+    return RSR_OK;
+}
+
+rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size) {
+    if (!host_buf || size < (int64_t)sizeof(SerialHeader)) { fail(RSR_EINVAL); return nullptr; }
+    SerialHeader hd;
+    std::memcpy(&hd, host_buf, sizeof(hd));
+    if (hd.magic != kSerialMagic || hd.version != kSerialVersion || hd.total_bytes != size) {
+        fail(RSR_EINVAL);
+        return nullptr;
+    }
+    // the geometry has to be one rsr_preprocess could have produced
+    const bool dense = hd.kind == RSR_DENSE_TERNARY_P2;
+    bool ok = (dense || is_rsr_kind(hd.kind)) && hd.rows >= 1 && hd.rows <= (int64_t)1 << 30 &&
+              hd.cols >= 1 && hd.cols <= rsr::kMaxCols;
+    if (ok && dense) {
+        const int64_t ntiles = (hd.cols + rsr::kDenseTileCols - 1) / rsr::kDenseTileCols;
+        ok = hd.row_bytes == ntiles * (rsr::kDenseTileCols / 4);
+    } else if (ok) {
+        const bool fused = hd.kind == RSR_TERNARY_FUSED;
+        ok = hd.k >= 1 && hd.k <= (fused ? 10 : 15) && hd.base == (fused ? 3 : 2) &&
+             hd.npass == (hd.kind == RSR_TERNARY_2PASS ? 2 : 1) && hd.W >= 1 && hd.W <= rsr::kMaxWaves &&
+             (hd.H == 1 || hd.H == 2 || hd.H == 4) &&
+             hd.enc == (hd.cols <= rsr::kSmallCols ? rsr::kEncSmall : rsr::kEncBig);
+        if (ok) {
+            ok = hd.P == ipow(hd.base, hd.k) && hd.nb == (hd.rows + hd.k - 1) / hd.k &&
+                 rsr::matvec_lds_bytes(hd.P, hd.cols, 4, rsr::kMaxWaves) <= rsr::kLdsBytes;
+            for (int ps = 0; ok && ps < hd.npass; ++ps)
+                ok = hd.C[ps] >= 1 && hd.C[ps] * rsr::kLoad * hd.H <= 4 * (hd.cols + hd.P) + rsr::kLoad * hd.H;
+        }
+    }
+    if (!ok) { fail(RSR_EINVAL); return nullptr; }
+
+    rsr_handle_s *h = new (std::nothrow) rsr_handle_s();
+    if (!h) { fail(RSR_ENOMEM); return nullptr; }
+    h->magic = rsr::kMagic;
+    h->kind = hd.kind; h->k = hd.k; h->base = hd.base; h->npass = hd.npass;
+    h->W = hd.W; h->H = hd.H; h->enc = hd.enc;
+    h->rows = hd.rows; h->cols = hd.cols; h->nb = hd.nb; h->P = hd.P; h->row_bytes = hd.row_bytes;
+    for (int ps = 0; ps < 2; ++ps) { h->pass[ps].C = hd.C[ps]; h->pass[ps].sign = hd.sign[ps]; }
+    if (!dense) {
+        const int64_t chunks[2] = {hd.C[0], hd.C[1]};
+        rsr::make_fold_shape(h->base, h->k, h->P, h->W, chunks, h->npass, &h->fold);
+    }
+    int rc = RSR_OK;
+    if (hipGetDevice(&h->device) != hipSuccess) rc = RSR_EHIP;
+    const std::vector<Piece> pieces = pieces_of(h);
+    int64_t need = (int64_t)sizeof(SerialHeader);
+    for (const Piece &pc : pieces) need += (int64_t)pc.bytes;
+    if (rc == RSR_OK && need != size) rc = RSR_EINVAL;
+    const unsigned char *in = static_cast<const unsigned char *>(host_buf);
+    size_t at = sizeof(SerialHeader);
+    for (size_t i = 0; rc == RSR_OK && i < pieces.size(); ++i) {
+        hipError_t e = hipMalloc(pieces[i].dev, pieces[i].bytes ? pieces[i].bytes : 1);
+        if (e == hipSuccess) e = hipMemcpy(*pieces[i].dev, in + at, pieces[i].bytes, hipMemcpyHostToDevice);
+        if (e != hipSuccess) rc = hip_code(e);
+        at += pieces[i].bytes;
+    }
+    if (rc != RSR_OK) {
+        (void)hipGetLastError();
+        free_handle(h);
+        fail(rc);
+        return nullptr;
+    }
+    g_last_error = RSR_OK;
+    return h;
+}
 
 int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void *out, int batch,
                   int64_t ldv, int64_t ldo, void *stream) {

@@ -85,6 +85,7 @@ hipError_t launch_stream_len(const uint32_t *off, int64_t nb, int64_t cols, int6
 hipError_t launch_pack_stream(const uint16_t *pi, const uint32_t *off, int64_t nb, int64_t cols,
                               int64_t P, int64_t C, int H, int enc, uint16_t *scratch,
                               uint16_t *entries, uint16_t *codes, int *err_flag);
+hipError_t launch_transpose(const int8_t *M, int64_t rows, int64_t cols, int8_t *T);
 hipError_t launch_pack2(const int8_t *M, int64_t rows, int64_t cols, int64_t row_bytes,
                         uint8_t *packed, int *err_flag);
 

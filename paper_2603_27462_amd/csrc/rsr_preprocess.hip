@@ -319,6 +319,24 @@ __global__ __launch_bounds__(kThreads) void k_finalize_stream(
 
 int grid_for_blocks(int64_t nb) { return (int)(nb < 4096 ? nb : 4096); }
 
+// T[j][i] = M[i][j] through 64 x 64 tiles in LDS (coalesced on both sides).
+__global__ __launch_bounds__(256) void k_transpose_i8(const int8_t *__restrict__ M, int64_t rows,
+                                                      int64_t cols, int8_t *__restrict__ T) {
+    __shared__ int8_t tile[64][65];
+    const int64_t tiles_x = (cols + 63) / 64;
+    const int64_t ti = blockIdx.x / tiles_x, tj = blockIdx.x % tiles_x;
+    const int x = threadIdx.x & 63, y0 = threadIdx.x >> 6;
+    for (int y = y0; y < 64; y += 4) {
+        const int64_t i = ti * 64 + y, j = tj * 64 + x;
+        tile[y][x] = (i < rows && j < cols) ? M[i * cols + j] : (int8_t)0;
+    }
+    __syncthreads();
+    for (int y = y0; y < 64; y += 4) {
+        const int64_t j = tj * 64 + y, i = ti * 64 + x;
+        if (i < rows && j < cols) T[j * rows + i] = tile[x][y];
+    }
+}
+
 }  // namespace
 
 hipError_t launch_encode(const int8_t *M, int64_t rows, int64_t cols, int k, int mode,
@@ -352,6 +370,12 @@ hipError_t launch_sort(const uint16_t *code, int64_t nb, int64_t cols, int k, in
         hipLaunchKernelGGL(k_sort<9>, dim3(grid_for_blocks(nb)), dim3(kThreads), lds, 0, code, nb,
                            n, passes, P, pi, off);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_transpose(const int8_t *M, int64_t rows, int64_t cols, int8_t *T) {
+    const int64_t tiles = ((rows + 63) / 64) * ((cols + 63) / 64);
+    hipLaunchKernelGGL(k_transpose_i8, dim3((unsigned)tiles), dim3(256), 0, 0, M, rows, cols, T);
     return hipGetLastError();
 }
 

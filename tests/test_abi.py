@@ -30,6 +30,17 @@ def test_error_strings_without_gpu():
     assert rsr.rsr_error_string(99) == "unknown error"
 
 
+def test_deserialize_rejects_what_it_did_not_write():
+    # header checks run on the host, before any device call
+    import numpy as np
+    import pytest
+    for blob in (np.zeros(16, np.uint8), np.zeros(4096, np.uint8),
+                 np.frombuffer(b"RSRS" + bytes(200), dtype=np.uint8)):
+        with pytest.raises(rsr.RsrError) as e:
+            rsr.rsr_deserialize(blob)
+        assert e.value.code == 1
+
+
 def test_no_oracle_in_product():
     # the product never imports the oracle
     pkg = os.path.dirname(rsr.__file__)

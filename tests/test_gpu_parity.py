@@ -172,6 +172,48 @@ def test_batch_many_blocks(kind, bf16, pad, batch):
         assert np.array_equal(got[i, :rows].astype(np.float64), want), "vector %d" % i
 
 
+@pytest.mark.parametrize("kind,k", [(rsr.RSR_TERNARY_FUSED, 6), (rsr.RSR_TERNARY_2PASS, 5),
+                                    (rsr.RSR_BINARY, 8), (rsr.RSR_DENSE_TERNARY_P2, 0)])
+def test_serialize_round_trip(kind, k):
+    rows, cols = 203, 1500
+    M = _matrix(kind, rows, cols, 55)
+    h = rsr.rsr_preprocess(_dev(M), k, kind)
+    blob = rsr.rsr_serialize(h)
+    h2 = rsr.rsr_deserialize(blob.tobytes())
+    assert (h2.rows, h2.cols, h2.k, h2.kind) == (rows, cols, k, kind)
+    assert np.array_equal(rsr.rsr_serialize(h2), blob)
+    if kind == rsr.RSR_DENSE_TERNARY_P2:
+        assert np.array_equal(rsr.rsr_get_packed(h2), oracle.pack2(M))
+    else:
+        _check_artifacts(h2, oracle.preprocess(M, k, KINDS[kind]))
+    v = _dev(gen.normal_f32(cols, seed=8))
+    assert torch.equal(rsr.rsr_matvec(h, v), rsr.rsr_matvec(h2, v))      # same stream, same bits
+    rsr.rsr_destroy(h)
+    _check_matvec(h2, M, cols, 9)                                          # and it outlives h
+    bad = blob.copy()
+    bad[8] ^= 0xFF                                                         # kind field
+    with pytest.raises(rsr.RsrError):
+        rsr.rsr_deserialize(bad)
+    with pytest.raises(rsr.RsrError):
+        rsr.rsr_deserialize(blob[:-7])
+
+
+@pytest.mark.parametrize("kind,k", [(rsr.RSR_TERNARY_FUSED, 5), (rsr.RSR_BINARY, 7),
+                                    (rsr.RSR_DENSE_TERNARY_P2, 0)])
+def test_transposed_handle(kind, k):
+    # the row-vector product v^T M: the handle of M^T against the oracle on M^T
+    rows, cols = 300, 130
+    M = _matrix(kind, rows, cols, 66)
+    h = rsr.rsr_preprocess_transposed(_dev(M), k, kind)
+    assert (h.rows, h.cols) == (cols, rows)
+    Mt = np.ascontiguousarray(M.T)
+    if kind == rsr.RSR_DENSE_TERNARY_P2:
+        assert np.array_equal(rsr.rsr_get_packed(h), oracle.pack2(Mt))
+    else:
+        _check_artifacts(h, oracle.preprocess(Mt, k, KINDS[kind]))
+    _check_matvec(h, Mt, rows, 12)
+
+
 def test_second_stream():
     rows, cols = 64, 2048
     M = _matrix(rsr.RSR_BINARY, rows, cols, 41)
