@@ -134,6 +134,66 @@ __device__ __forceinline__ void tail_store2(uint32_t d, float base, float s0, fl
     }
 }
 
+// Eight entries (dwords d0..d3) at once, small encoding: the eight tail masks and the eight
+// sums base + s are computed first, as independent instructions, so that the part that has
+// to run in order -- set the execution mask, store, advance the pointer -- is three
+// instructions per entry with a single vector instruction in the dependency chain.
+__device__ __forceinline__ void tail_store8_small(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t d3,
+                                                  float base, const float (&s)[8], uint32_t &ptr) {
+    uint64_t m0, m1, m2, m3, m4, m5, m6, m7;
+    float t0, t1, t2, t3, t4, t5, t6, t7;
+    asm volatile(
+        "v_cmp_gt_i16 %[m0], 0, %[d0]\n\t"
+        "v_cmp_gt_i32 %[m1], 0, %[d0]\n\t"
+        "v_cmp_gt_i16 %[m2], 0, %[d1]\n\t"
+        "v_cmp_gt_i32 %[m3], 0, %[d1]\n\t"
+        "v_cmp_gt_i16 %[m4], 0, %[d2]\n\t"
+        "v_cmp_gt_i32 %[m5], 0, %[d2]\n\t"
+        "v_cmp_gt_i16 %[m6], 0, %[d3]\n\t"
+        "v_cmp_gt_i32 %[m7], 0, %[d3]\n\t"
+        "v_add_f32 %[t0], %[b], %[s0]\n\t"
+        "v_add_f32 %[t1], %[b], %[s1]\n\t"
+        "v_add_f32 %[t2], %[b], %[s2]\n\t"
+        "v_add_f32 %[t3], %[b], %[s3]\n\t"
+        "v_add_f32 %[t4], %[b], %[s4]\n\t"
+        "v_add_f32 %[t5], %[b], %[s5]\n\t"
+        "v_add_f32 %[t6], %[b], %[s6]\n\t"
+        "v_add_f32 %[t7], %[b], %[s7]\n\t"
+        "s_mov_b64 exec, %[m0]\n\t"
+        "ds_write_b32 %[p], %[t0]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, %[m1]\n\t"
+        "ds_write_b32 %[p], %[t1]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, %[m2]\n\t"
+        "ds_write_b32 %[p], %[t2]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, %[m3]\n\t"
+        "ds_write_b32 %[p], %[t3]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, %[m4]\n\t"
+        "ds_write_b32 %[p], %[t4]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, %[m5]\n\t"
+        "ds_write_b32 %[p], %[t5]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, %[m6]\n\t"
+        "ds_write_b32 %[p], %[t6]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, %[m7]\n\t"
+        "ds_write_b32 %[p], %[t7]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, -1"
+        : [p] "+v"(ptr), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
+          [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7), [m0] "=&s"(m0),
+          [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3), [m4] "=&s"(m4), [m5] "=&s"(m5),
+          [m6] "=&s"(m6), [m7] "=&s"(m7)
+        : [d0] "v"(d0), [d1] "v"(d1), [d2] "v"(d2), [d3] "v"(d3), [b] "v"(base), [s0] "v"(s[0]),
+          [s1] "v"(s[1]), [s2] "v"(s[2]), [s3] "v"(s[3]), [s4] "v"(s[4]), [s5] "v"(s[5]),
+          [s6] "v"(s[6]), [s7] "v"(s[7])
+        : "memory");
+}
+
 __device__ __forceinline__ void lds_drain() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 template <typename VT>

@@ -622,9 +622,12 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         uint32_t ptr = e_at + code * 4u;
 #pragma unroll
         for (int h = 0; h < H; ++h) {
+            if (ENC == kEncSmall) {
+                tail_store8_small(d[h][0], d[h][1], d[h][2], d[h][3], base, s[h], ptr);
+            } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                tail_store2<ENC>(d[h][j], base, s[h][2 * j], s[h][2 * j + 1], ptr);
+                for (int j = 0; j < 4; ++j)
+                    tail_store2<ENC>(d[h][j], base, s[h][2 * j], s[h][2 * j + 1], ptr);
             }
         }
         total = lane63(incl);
