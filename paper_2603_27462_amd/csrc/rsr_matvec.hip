@@ -456,6 +456,35 @@ __global__ __launch_bounds__(1024) void k_rsr_matvec(const PassArgs a0, const vo
 // nothing loops.  Same phases as run_pass, with every load of the pass requested up front
 // and the scatter-phase constants prepared while they are in flight.  MULTI: the workgroup
 // multiplies several vectors in turn with the stream kept in registers.
+
+// What a wave loads of its chunk: H 16-byte pieces of stream per lane, the strip's start
+// code, and the wave-total sign of lane % 16's row.
+template <int H>
+struct StreamRegs {
+    uint4 q[H];
+    uint32_t code;
+    int8_t wsg8;
+};
+
+// The stream is read once: non-temporal loads keep it out of the way of v and the tables.
+// Waves without a chunk (w >= C) load the last chunk and ignore it: no branch, so nothing
+// delays the requests.
+template <int H>
+__device__ __forceinline__ void load_stream(StreamRegs<H> &r, const uint16_t *__restrict__ entries,
+                                            const uint16_t *__restrict__ codes,
+                                            const int8_t *__restrict__ wsign, int C, long long b,
+                                            int W, int w, int lane) {
+    const int wc = min(w, C - 1);
+    const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + ((b * C + wc) * H) * 64 + lane;
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        const u32x4 t = __builtin_nontemporal_load(&ep[h * 64]);
+        r.q[h] = make_uint4(t.x, t.y, t.z, t.w);
+    }
+    r.code = __builtin_nontemporal_load(&codes[(b * C + wc) * 64 + lane]);
+    r.wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
+}
+
 struct SecondPass {
     const uint16_t *entries;
     const uint16_t *codes;
@@ -464,14 +493,17 @@ struct SecondPass {
     float sign;
 };
 
-template <typename VT, int H, int ENC, bool FIRST, bool MULTI>
+// NEXT: the pass also requests the stream of the pass that follows it (two-pass kinds),
+// behind its own loads, into `next`; PRE: the pass finds its own stream in `pre`.
+template <typename VT, int H, int ENC, bool FIRST, bool MULTI, bool NEXT, bool PRE>
 __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries,
                                             const uint16_t *__restrict__ codes,
                                             const int8_t *__restrict__ wsign, int C, float sign,
                                             const void *__restrict__ v, long long ldv, int n_in,
                                             int W, const FoldArgs &f, float *out, long long ldo,
                                             int n_out, float scale, const OutArgs &o, int vec0,
-                                            int nvec_arg) {
+                                            int nvec_arg, const SecondPass *nextp,
+                                            StreamRegs<H> *next, const StreamRegs<H> *pre) {
     const int nvec = MULTI ? nvec_arg : 1;
     const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
     const uint32_t corr_at = vbytes;                    // float [16 waves][16 rows]
@@ -490,7 +522,6 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     // the stream ------------------------------------------------------------------------------
     const uint2 share = make_uint2(f.fshare[tid], 0u);
     const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
-    const int8_t wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
     // vectors vec0 .. vec0+nvec-1 are multiplied one after the other with the same stream
     // registers (nvec > 1 only in the first pass of one-pass kinds)
     const long long vstride = ldv * (long long)sizeof(VT);
@@ -509,18 +540,17 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         s2 = v16[min(j_2, n16 - 1)];
         s3 = v16[min(j_3, n16 - 1)];
     }
-    // the stream is read once: non-temporal loads keep it out of the way of v and the tables.
-    // Waves without a chunk (w >= C) load the last chunk and ignore it: no branch, so
-    // nothing delays the requests.
+    StreamRegs<H> own;
+    if (PRE)
+        own = *pre;
+    else
+        load_stream<H>(own, entries, codes, wsign, C, b, W, w, lane);
+    if (NEXT) load_stream_second<H>(*next, nextp, b, W, w, lane);
     uint4 q[H];
-    const int wc = min(w, C - 1);
-    const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + ((b * C + wc) * H) * 64 + lane;
 #pragma unroll
-    for (int h = 0; h < H; ++h) {
-        const u32x4 t = __builtin_nontemporal_load(&ep[h * 64]);
-        q[h] = make_uint4(t.x, t.y, t.z, t.w);
-    }
-    uint32_t code = __builtin_nontemporal_load(&codes[(b * C + wc) * 64 + lane]);
+    for (int h = 0; h < H; ++h) q[h] = own.q[h];
+    uint32_t code = own.code;
+    const int8_t wsg8 = own.wsg8;
 
     // ---- work that needs no stream data, done while the loads are in flight ----------------
     ScatterPrep sp;
@@ -656,6 +686,12 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     }
 }
 
+template <int H>
+__device__ __forceinline__ void load_stream_second(StreamRegs<H> &r, const SecondPass *p, long long b,
+                                                   int W, int w, int lane) {
+    load_stream<H>(r, p->entries, p->codes, p->wsign, p->C, b, W, w, lane);
+}
+
 template <typename VT, int H, int ENC, int NPASS, bool MULTI>
 __global__ __launch_bounds__(1024, 4) void k_rsr_matvec1(
     const uint16_t *__restrict__ entries0, const uint16_t *__restrict__ codes0,
@@ -673,12 +709,19 @@ __global__ __launch_bounds__(1024, 4) void k_rsr_matvec1(
     // other, keeping the stream in registers; otherwise one vector per workgroup
     const int vec0 = MULTI ? blockIdx.y * o.vper : blockIdx.y;
     const int nvec = MULTI ? min(o.vper, o.batch - vec0) : 1;
-    single_pass<VT, H, ENC, true, MULTI>(entries0, codes0, wsign0, C0, sign0, v, ldv, n_in, W, f,
-                                         o.out, o.ldo, o.n_out, o.scale, o, vec0, nvec);
+    // two passes: the second pass's stream is requested behind the first one's loads (kept in
+    // registers through the first pass; not for the largest chunk size, which has none to spare)
+    constexpr bool kAhead = NPASS == 2 && H <= 2;
+    StreamRegs<H> second;
+    single_pass<VT, H, ENC, true, MULTI, kAhead, false>(entries0, codes0, wsign0, C0, sign0, v, ldv,
+                                                        n_in, W, f, o.out, o.ldo, o.n_out, o.scale, o,
+                                                        vec0, nvec, &a1, &second, nullptr);
     if (NPASS == 2) {
         __syncthreads();
-        single_pass<VT, H, ENC, false, false>(a1.entries, a1.codes, a1.wsign, a1.C, a1.sign, v, ldv,
-                                              n_in, W, f, o.out, o.ldo, o.n_out, o.scale, o, vec0, 1);
+        single_pass<VT, H, ENC, false, false, false, kAhead>(a1.entries, a1.codes, a1.wsign, a1.C,
+                                                             a1.sign, v, ldv, n_in, W, f, o.out, o.ldo,
+                                                             o.n_out, o.scale, o, vec0, 1, nullptr,
+                                                             nullptr, &second);
     }
     RSR_STAMP(7);
 }
