@@ -89,7 +89,8 @@ rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, 
  *   stream hipStream_t passed as void*; NULL = the null stream
  *
  * Asynchronous on `stream`; allocates nothing and never synchronises, so it
- * may be captured into a HIP graph.  Calls on different streams with
+ * may be captured into a HIP graph.  The current device must be the one the
+ * handle was made on (RSR_EINVAL otherwise).  Calls on different streams with
  * different `out` may overlap.  Accumulation is float32.
  */
 int rsr_matvec(rsr_handle_t h, const void *v, void *out, void *stream);

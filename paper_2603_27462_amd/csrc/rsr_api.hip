@@ -445,6 +445,9 @@ int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void 
         return fail(RSR_EINVAL);
     if (batch > 65535) return fail(RSR_EUNSUPPORTED);
     if (batch > 1 && (ldv < h->cols || ldo < h->rows)) return fail(RSR_EINVAL);
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return fail(RSR_EHIP);
+    if (device != h->device) return fail(RSR_EINVAL);  // the handle's buffers live on another GPU
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     hipError_t e = (h->kind == RSR_DENSE_TERNARY_P2)
                        ? rsr::launch_dense_matvec(h, v, v_dtype, scale, static_cast<float *>(out),

@@ -209,16 +209,12 @@ __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
 template <typename VT, int WPG>
 hipError_t launch_w(const rsr_handle_s *h, const void *v, float scale, float *out, int batch,
                     int64_t ldv, int64_t ldo, hipStream_t stream, int nv, int slab_tiles, size_t lds) {
-    static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
+    static std::atomic<size_t> enabled[kMaxDevices];
     auto kern = k_dense_matvec<VT, WPG>;
     const int ntiles = (int)(h->row_bytes / (kDenseTileCols / 4));
     const int ngroups = (int)((h->rows + kDenseRows - 1) / kDenseRows);
-    if (lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_bytes = lds;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), lds, h->device, enabled))
+        return e;
     constexpr int gpw = kDenseWaves / WPG;
     hipLaunchKernelGGL(kern, dim3((unsigned)((ngroups + gpw - 1) / gpw), (unsigned)((batch + nv - 1) / nv)),
                        dim3(kDenseWaves * 64), lds, stream,

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "rsr.h"
 
 namespace rsr {
@@ -111,6 +113,20 @@ hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int W, uint3
                               uint32_t *fshare);
 hipError_t launch_wave_signs(int base, int k, const uint16_t *codes, int64_t nb, int64_t C, int W,
                              const FoldShape &fs, int pass, int8_t *wsign);
+
+// Dynamic LDS beyond 64 KiB has to be enabled per kernel and device.  `enabled` is the
+// kernel's table of the largest size enabled so far on each device (zero-initialised
+// static storage).  Concurrent callers may both set the attribute: harmless.
+constexpr int kMaxDevices = 64;
+inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, int device,
+                                     std::atomic<size_t> (&enabled)[kMaxDevices]) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    if (bytes <= enabled[device].load(std::memory_order_relaxed)) return hipSuccess;
+    const hipError_t e =
+        hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess) enabled[device].store(bytes, std::memory_order_relaxed);
+    return e;
+}
 
 // LDS bytes the RSR multiply kernel needs: v and its zero slot, the wave-total terms,
 // E[P] followed by a row of zeros (at most one per thread), and one level-1 sum per thread.

@@ -457,13 +457,12 @@ __global__ __launch_bounds__(1024) void k_rsr_matvec(const PassArgs a0, const vo
 // and the scatter-phase constants prepared while they are in flight.  MULTI: the workgroup
 // multiplies several vectors in turn with the stream kept in registers.
 
-// What a wave loads of its chunk: H 16-byte pieces of stream per lane, the strip's start
-// code, and the wave-total sign of lane % 16's row.
+// What a wave loads of its chunk: H 16-byte pieces of stream per lane and the strip's start
+// code.
 template <int H>
 struct StreamRegs {
     uint4 q[H];
     uint32_t code;
-    int8_t wsg8;
 };
 
 // The stream is read once: non-temporal loads keep it out of the way of v and the tables.
@@ -471,9 +470,8 @@ struct StreamRegs {
 // delays the requests.
 template <int H>
 __device__ __forceinline__ void load_stream(StreamRegs<H> &r, const uint16_t *__restrict__ entries,
-                                            const uint16_t *__restrict__ codes,
-                                            const int8_t *__restrict__ wsign, int C, long long b,
-                                            int W, int w, int lane) {
+                                            const uint16_t *__restrict__ codes, int C, long long b,
+                                            int w, int lane) {
     const int wc = min(w, C - 1);
     const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + ((b * C + wc) * H) * 64 + lane;
 #pragma unroll
@@ -482,7 +480,6 @@ __device__ __forceinline__ void load_stream(StreamRegs<H> &r, const uint16_t *__
         r.q[h] = make_uint4(t.x, t.y, t.z, t.w);
     }
     r.code = __builtin_nontemporal_load(&codes[(b * C + wc) * 64 + lane]);
-    r.wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
 }
 
 struct SecondPass {
@@ -522,6 +519,8 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     // the stream ------------------------------------------------------------------------------
     const uint2 share = make_uint2(f.fshare[tid], 0u);
     const uint32_t wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
+    // (requested before the stream: it is converted while the stream is still in flight)
+    const int8_t wsg8 = wsign[(b * W + w) * 16 + (lane & 15)];
     // vectors vec0 .. vec0+nvec-1 are multiplied one after the other with the same stream
     // registers (nvec > 1 only in the first pass of one-pass kinds)
     const long long vstride = ldv * (long long)sizeof(VT);
@@ -544,13 +543,12 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     if (PRE)
         own = *pre;
     else
-        load_stream<H>(own, entries, codes, wsign, C, b, W, w, lane);
-    if (NEXT) load_stream_second<H>(*next, nextp, b, W, w, lane);
+        load_stream<H>(own, entries, codes, C, b, w, lane);
+    if (NEXT) load_stream_second<H>(*next, nextp, b, w, lane);
     uint4 q[H];
 #pragma unroll
     for (int h = 0; h < H; ++h) q[h] = own.q[h];
     uint32_t code = own.code;
-    const int8_t wsg8 = own.wsg8;
 
     // ---- work that needs no stream data, done while the loads are in flight ----------------
     ScatterPrep sp;
@@ -688,8 +686,8 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
 
 template <int H>
 __device__ __forceinline__ void load_stream_second(StreamRegs<H> &r, const SecondPass *p, long long b,
-                                                   int W, int w, int lane) {
-    load_stream<H>(r, p->entries, p->codes, p->wsign, p->C, b, W, w, lane);
+                                                   int w, int lane) {
+    load_stream<H>(r, p->entries, p->codes, p->C, b, w, lane);
 }
 
 template <typename VT, int H, int ENC, int NPASS, bool MULTI>
@@ -730,7 +728,7 @@ struct LaunchArgs {
     PassArgs a0, a1;
     const void *v;
     long long ldv;
-    int n_in, W, npass, nblocks, batch;
+    int n_in, W, npass, nblocks, batch, device;
     FoldArgs f;
     OutArgs o;
     size_t lds;
@@ -740,14 +738,10 @@ struct LaunchArgs {
 
 template <typename VT, int H, int ENC, int NPASS, bool MULTI>
 hipError_t launch_single(const LaunchArgs &x) {
-    static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
+    static std::atomic<size_t> enabled[kMaxDevices];
     auto kern = k_rsr_matvec1<VT, H, ENC, NPASS, MULTI>;
-    if (x.lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)x.lds);
-        if (e != hipSuccess) return e;
-        attr_bytes = x.lds;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), x.lds, x.device, enabled))
+        return e;
     SecondPass a1;
     a1.entries = x.a1.entries;
     a1.codes = x.a1.codes;
@@ -767,14 +761,10 @@ hipError_t launch(const LaunchArgs &x) {
         if (NPASS == 1 && x.o.vper > 1) return launch_single<VT, H, ENC, 1, true>(x);
         return launch_single<VT, H, ENC, NPASS, false>(x);
     }
-    static size_t attr_bytes = 0;  // largest dynamic LDS size enabled for this kernel so far
+    static std::atomic<size_t> enabled[kMaxDevices];
     auto kern = k_rsr_matvec<VT, H, ENC, NPASS>;
-    if (x.lds > attr_bytes) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)x.lds);
-        if (e != hipSuccess) return e;
-        attr_bytes = x.lds;
-    }
+    if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), x.lds, x.device, enabled))
+        return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)x.nblocks, (unsigned)x.batch),
                        dim3(x.W * 64), x.lds, x.stream, x.a0, x.v, x.ldv, x.n_in, x.W, x.f, x.a1, x.o);
     return hipGetLastError();
@@ -972,6 +962,7 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     x.W = h->W;
     x.npass = h->npass;
     x.nblocks = (int)h->nb;
+    x.device = h->device;
     x.batch = batch;
     x.f.fpack = h->fpack;
     x.f.fshare = h->fshare;
