@@ -491,7 +491,7 @@ struct SecondPass {
 };
 
 // NEXT: the pass also requests the stream of the pass that follows it (two-pass kinds),
-// behind its own loads, into `next`; PRE: the pass finds its own stream in `pre`.
+// after its first barrier, into `next`; PRE: the pass finds its own stream in `pre`.
 template <typename VT, int H, int ENC, bool FIRST, bool MULTI, bool NEXT, bool PRE>
 __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries,
                                             const uint16_t *__restrict__ codes,
@@ -544,7 +544,6 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
         own = *pre;
     else
         load_stream<H>(own, entries, codes, C, b, w, lane);
-    if (NEXT) load_stream_second<H>(*next, nextp, b, w, lane);
     uint4 q[H];
 #pragma unroll
     for (int h = 0; h < H; ++h) q[h] = own.q[h];
@@ -601,6 +600,9 @@ __device__ __forceinline__ void single_pass(const uint16_t *__restrict__ entries
     __syncthreads();
     RSR_STAMP(1);
     RSR_STOP(1);
+    // the following pass's stream is requested once this pass's own data is here, so that
+    // the two do not compete for HBM, and arrives while this pass computes
+    if (NEXT && vi == 0) load_stream_second<H>(*next, nextp, b, w, lane);
     if (MULTI && FIRST) {  // from here on vg is the next vector
         vg += vstride;
         v16 = reinterpret_cast<const u32x4 *>(vg);
@@ -707,8 +709,8 @@ __global__ __launch_bounds__(1024, 4) void k_rsr_matvec1(
     // other, keeping the stream in registers; otherwise one vector per workgroup
     const int vec0 = MULTI ? blockIdx.y * o.vper : blockIdx.y;
     const int nvec = MULTI ? min(o.vper, o.batch - vec0) : 1;
-    // two passes: the second pass's stream is requested behind the first one's loads (kept in
-    // registers through the first pass; not for the largest chunk size, which has none to spare)
+    // two passes: the second pass's stream is requested while the first pass computes (kept in
+    // registers meanwhile; not for the largest chunk size, which has none to spare)
     constexpr bool kAhead = NPASS == 2 && H <= 2;
     StreamRegs<H> second;
     single_pass<VT, H, ENC, true, MULTI, kAhead, false>(entries0, codes0, wsign0, C0, sign0, v, ldv,
