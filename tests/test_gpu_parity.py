@@ -214,6 +214,22 @@ def test_transposed_handle(kind, k):
     _check_matvec(h, Mt, rows, 12)
 
 
+def test_linear_module():
+    from paper_2603_27462_amd.linear import RsrLinear
+    rows, cols = 96, 640
+    M = gen.ternary_matrix(rows, cols, 0.4, 91)
+    layer = RsrLinear(_dev(M), scale=0.25)                     # k chosen by the library
+    xi = np.stack([gen.integer_f32(cols, seed=700 + i) for i in range(6)]).reshape(2, 3, cols)
+    y = layer(_dev(xi).to(torch.bfloat16)).cpu().numpy()
+    assert y.shape == (2, 3, rows)
+    for a in range(2):
+        for b in range(3):
+            want = oracle.dense_matvec(M, xi[a, b].astype(np.float64), 0.25)
+            assert np.array_equal(y[a, b].astype(np.float64), want)
+    y1 = layer(_dev(xi[0, 0])).cpu().numpy()                   # a single float32 vector
+    assert np.array_equal(y1.astype(np.float64), oracle.dense_matvec(M, xi[0, 0].astype(np.float64), 0.25))
+
+
 def test_second_stream():
     rows, cols = 64, 2048
     M = _matrix(rsr.RSR_BINARY, rows, cols, 41)
