@@ -43,7 +43,9 @@ enum {
     RSR_EUNSUPPORTED = 3, /* valid request outside the limits stated below                 */
     RSR_ENOMEM = 4,       /* device or host allocation failed                              */
     RSR_EHIP = 5,         /* a HIP runtime call failed                                     */
-    RSR_EINTERNAL = 6     /* a self-check of the preprocessing output failed               */
+    RSR_EINTERNAL = 6,    /* a self-check of the preprocessing output failed               */
+    RSR_ESCRATCH = 7      /* rsr_preprocess_into: the input needs more temporary memory    */
+                          /* than the fixed scratch array (RSR_INTO_SCRATCH_BYTES)         */
 };
 
 /*
@@ -133,6 +135,36 @@ rsr_handle_t rsr_preprocess_transposed(const int8_t *M, int64_t rows, int64_t co
 int64_t rsr_serialized_size(rsr_handle_t h);
 int rsr_serialize(rsr_handle_t h, void *host_buf, int64_t capacity);
 rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size);
+
+/*
+ * rsr_preprocess_into -- rsr_preprocess for callers that cannot allocate device memory
+ * (serving loops that must not call hipMalloc, harnesses that forbid it, code that runs
+ * next to a HIP graph capture): preprocesses a new matrix of the SAME shape into the
+ * buffers of an existing handle, replacing the matrix it held.  Block height, kind and
+ * the multiply-kernel layout stay those of the handle.  Calls no hipMalloc / hipFree and
+ * no allocating library routine; the same kernels as rsr_preprocess run, and their
+ * temporaries (pattern codes, the stream in logical order, per-block lengths, flags)
+ * live in one fixed device array of RSR_INTO_SCRATCH_BYTES that the library holds on
+ * every GPU it runs on until the process ends.
+ *
+ *   h  a handle made by rsr_preprocess / rsr_deserialize on the current device
+ *   M  DEVICE int8 [rows][cols] with the handle's rows and cols; borrowed
+ *
+ * Temporary memory needed: 256 bytes for the dense kind; otherwise, each term rounded
+ * up to 256 bytes, 256 + 4*nb + 2*nb*cols + 2*nb*S with nb = ceil(rows/k) and S the
+ * stream slots per block of the handle (at most cols + P rounded up to 2048).  More than
+ * RSR_INTO_SCRATCH_BYTES: RSR_ESCRATCH, handle untouched.  A matrix whose stream needs
+ * more slots per block than the handle holds (more empty pattern groups than the matrix
+ * the handle was made from): RSR_EUNSUPPORTED; an entry outside the alphabet: RSR_EVALUE.
+ * After these two, and after RSR_EHIP, the handle's contents are unspecified and
+ * rsr_matvec refuses it (RSR_EINVAL) until a later rsr_preprocess_into succeeds.
+ *
+ * Runs on the null stream and synchronises before returning.  All calls on one GPU share
+ * the one scratch array: calls that overlap on a GPU (from several threads) race, and so
+ * does a multiply on the same handle that overlaps the call.
+ */
+#define RSR_INTO_SCRATCH_BYTES (32 * 1024 * 1024)
+int rsr_preprocess_into(rsr_handle_t h, const int8_t *M);
 
 /* Frees the handle and its device buffers.  NULL is allowed. */
 void rsr_destroy(rsr_handle_t h);

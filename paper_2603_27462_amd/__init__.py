@@ -7,7 +7,7 @@ library cannot be loaded every call raises.
 from .binding import (  # noqa: F401
     RSR_BINARY, RSR_TERNARY_2PASS, RSR_TERNARY_FUSED, RSR_DENSE_TERNARY_P2,
     RSR_F32, RSR_BF16, RsrError, Handle, load_library, exported_symbols,
-    rsr_preprocess, rsr_preprocess_transposed, rsr_matvec, rsr_matvec_ex, rsr_destroy,
+    rsr_preprocess, rsr_preprocess_transposed, rsr_preprocess_into, rsr_matvec, rsr_matvec_ex, rsr_destroy,
     rsr_serialize, rsr_deserialize, rsr_last_error,
     rsr_error_string, rsr_get_perm, rsr_get_offsets, rsr_get_packed,
     rsr_num_blocks, rsr_block_height, rsr_num_patterns, rsr_num_passes, rsr_algorithmic_bytes,

@@ -23,7 +23,7 @@ exported_symbols = [
     "rsr_preprocess_transposed", "rsr_serialized_size", "rsr_serialize", "rsr_deserialize",
     "rsr_num_blocks", "rsr_block_height", "rsr_num_patterns", "rsr_num_passes",
     "rsr_algorithmic_bytes",
-    "rsr_kernel_name",
+    "rsr_kernel_name", "rsr_preprocess_into",
 ]
 
 
@@ -73,6 +73,8 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rsr_num_passes.argtypes = [vp]
     lib.rsr_preprocess_transposed.restype = vp
     lib.rsr_preprocess_transposed.argtypes = [vp, i64, i64, ci, ci]
+    lib.rsr_preprocess_into.restype = ci
+    lib.rsr_preprocess_into.argtypes = [vp, vp]
     lib.rsr_serialized_size.restype = i64
     lib.rsr_serialized_size.argtypes = [vp]
     lib.rsr_serialize.restype = ci
@@ -144,6 +146,19 @@ def rsr_preprocess_transposed(M, k: int, kind: int) -> Handle:
     if not ptr:
         raise RsrError(rsr_last_error(), "rsr_preprocess_transposed")
     return Handle(ptr, cols, rows, int(load_library().rsr_block_height(ptr)), int(kind))
+
+
+def rsr_preprocess_into(h: Handle, M) -> None:
+    """Replace the matrix of h by M (same shape) without allocating device memory."""
+    import torch
+    if not (isinstance(M, torch.Tensor) and M.is_cuda and M.dtype == torch.int8 and
+            tuple(M.shape) == (h.rows, h.cols) and M.is_contiguous()):
+        raise TypeError("M must be a contiguous int8 CUDA tensor [rows][cols] of the handle's shape")
+    with torch.cuda.device(M.device):
+        torch.cuda.current_stream().synchronize()
+        rc = load_library().rsr_preprocess_into(h.ptr, M.data_ptr())
+    if rc:
+        raise RsrError(rc, "rsr_preprocess_into")
 
 
 def rsr_serialize(h: Handle) -> np.ndarray:

@@ -58,59 +58,102 @@ int hip_code(hipError_t e) { return e == hipErrorOutOfMemory ? RSR_ENOMEM : RSR_
         if (e_ != hipSuccess) { rc = hip_code(e_); goto done; } \
     } while (0)
 
+// Device memory a preprocessing run needs besides the handle's own buffers: the pattern
+// codes of every (block, column), the stream in logical order, one length per block, and
+// a few words of flags (kFlagErr: entry outside the alphabet / self-check; kFlagLen + pass:
+// longest stream of a block).
+struct Temps {
+    uint16_t *code = nullptr;     // [nb][cols]
+    uint16_t *logical = nullptr;  // [nb][max over passes of C * chunk]
+    uint32_t *lens = nullptr;     // [nb]
+    int *flags = nullptr;         // [kFlagWords]
+};
+constexpr int kFlagErr = 0, kFlagLen = 1, kFlagWords = 64;
+
+int read_flags(const Temps &t, int (&host)[kFlagWords]) {
+    return hipMemcpy(host, t.flags, sizeof(host), hipMemcpyDeviceToHost) == hipSuccess ? RSR_OK
+                                                                                       : RSR_EHIP;
+}
+
+int run_dense(rsr_handle_s *h, const int8_t *M, const Temps &t) {
+    int host[kFlagWords];
+    if (rsr::launch_fill_u32(reinterpret_cast<uint32_t *>(t.flags), 0u, kFlagWords) != hipSuccess ||
+        rsr::launch_pack2(M, h->rows, h->cols, h->row_bytes, h->packed, t.flags + kFlagErr) != hipSuccess)
+        return RSR_EHIP;
+    if (int rc = read_flags(t, host)) return rc;
+    return host[kFlagErr] ? RSR_EVALUE : RSR_OK;
+}
+
+// encode -> counting sort -> stream length, per pass; max_len[ps] = longest stream of a block
+int run_sort_passes(rsr_handle_s *h, const int8_t *M, const Temps &t, int64_t (&max_len)[2]) {
+    static const int modes[3][2] = {{rsr::MODE_BINARY, 0}, {rsr::MODE_POS, rsr::MODE_NEG},
+                                    {rsr::MODE_FUSED3, 0}};
+    int host[kFlagWords];
+    if (rsr::launch_fill_u32(reinterpret_cast<uint32_t *>(t.flags), 0u, kFlagWords) != hipSuccess)
+        return RSR_EHIP;
+    for (int ps = 0; ps < h->npass; ++ps) {
+        rsr::PassData &pd = h->pass[ps];
+        pd.sign = (ps == 0) ? 1.0f : -1.0f;
+        if (rsr::launch_encode(M, h->rows, h->cols, h->k, modes[h->kind][ps], t.code,
+                               t.flags + kFlagErr) != hipSuccess ||
+            rsr::launch_sort(t.code, h->nb, h->cols, h->k, h->base, h->P, pd.pi, pd.off) != hipSuccess ||
+            rsr::launch_stream_len(pd.off, h->nb, h->cols, h->P, t.lens,
+                                   reinterpret_cast<uint32_t *>(t.flags + kFlagLen + ps)) != hipSuccess)
+            return RSR_EHIP;
+    }
+    if (int rc = read_flags(t, host)) return rc;
+    if (host[kFlagErr]) return RSR_EVALUE;
+    max_len[0] = (uint32_t)host[kFlagLen];
+    max_len[1] = (uint32_t)host[kFlagLen + 1];
+    return RSR_OK;
+}
+
+// the stream and the small tables of the multiply kernel, in the layout the handle records
+int run_pack_passes(rsr_handle_s *h, const Temps &t) {
+    int host[kFlagWords];
+    if (rsr::launch_fold_tables(h->base, h->k, h->fold, h->W, h->fpack, h->fshare) != hipSuccess)
+        return RSR_EHIP;
+    for (int ps = 0; ps < h->npass; ++ps) {
+        rsr::PassData &pd = h->pass[ps];
+        if (rsr::launch_pack_stream(pd.pi, pd.off, h->nb, h->cols, h->P, pd.C, h->H, h->enc, t.logical,
+                                    pd.entries, pd.codes, t.flags + kFlagErr) != hipSuccess ||
+            rsr::launch_wave_signs(h->base, h->k, pd.codes, h->nb, pd.C, h->W, h->fold, ps,
+                                   pd.wsign) != hipSuccess)
+            return RSR_EHIP;
+    }
+    if (int rc = read_flags(t, host)) return rc;
+    return host[kFlagErr] ? RSR_EINTERNAL : RSR_OK;
+}
+
 int preprocess_dense(rsr_handle_s *h, const int8_t *M) {
     int rc = RSR_OK;
-    int *err_flag = nullptr;
-    int host_flag = 0;
+    Temps t;
     const int64_t ntiles = (h->cols + rsr::kDenseTileCols - 1) / rsr::kDenseTileCols;
     h->row_bytes = ntiles * (rsr::kDenseTileCols / 4);
     const size_t bytes =
         (size_t)((h->rows + rsr::kDenseRows - 1) / rsr::kDenseRows) * rsr::kDenseRows * h->row_bytes;
     RSR_TRY(dev_alloc(&h->packed, bytes));
-    RSR_TRY(dev_alloc(&err_flag, 1));
-    RSR_TRY(hipMemsetAsync(err_flag, 0, sizeof(int), 0));
-    RSR_TRY(rsr::launch_pack2(M, h->rows, h->cols, h->row_bytes, h->packed, err_flag));
-    RSR_TRY(hipMemcpy(&host_flag, err_flag, sizeof(int), hipMemcpyDeviceToHost));
-    if (host_flag) rc = RSR_EVALUE;
+    RSR_TRY(dev_alloc(&t.flags, kFlagWords));
+    rc = run_dense(h, M, t);
 done:
-    if (err_flag) (void)hipFree(err_flag);
+    if (t.flags) (void)hipFree(t.flags);
     return rc;
 }
 
 int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
     int rc = RSR_OK;
-    uint16_t *code = nullptr, *scratch = nullptr;
-    uint32_t *lens = nullptr;
-    int *err_flag = nullptr;
-    int host_flag = 0;
+    Temps t;
     const int64_t nb = h->nb, cols = h->cols, P = h->P;
-    std::vector<uint32_t> host_lens((size_t)nb);
     int64_t max_len[2] = {0, 0};
-    static const int modes[3][2] = {{rsr::MODE_BINARY, 0}, {rsr::MODE_POS, rsr::MODE_NEG},
-                                    {rsr::MODE_FUSED3, 0}};
 
-    RSR_TRY(dev_alloc(&code, (size_t)(nb * cols)));
-    RSR_TRY(dev_alloc(&lens, (size_t)nb));
-    RSR_TRY(dev_alloc(&err_flag, 1));
-    RSR_TRY(hipMemsetAsync(err_flag, 0, sizeof(int), 0));
-
-    // encode -> counting sort -> stream length, per pass
+    RSR_TRY(dev_alloc(&t.code, (size_t)(nb * cols)));
+    RSR_TRY(dev_alloc(&t.lens, (size_t)nb));
+    RSR_TRY(dev_alloc(&t.flags, kFlagWords));
     for (int ps = 0; ps < h->npass; ++ps) {
-        rsr::PassData &pd = h->pass[ps];
-        pd.sign = (ps == 0) ? 1.0f : -1.0f;
-        RSR_TRY(dev_alloc(&pd.pi, (size_t)(nb * cols)));
-        RSR_TRY(dev_alloc(&pd.off, (size_t)(nb * (P + 1))));
-        RSR_TRY(rsr::launch_encode(M, h->rows, cols, h->k, modes[h->kind][ps], code, err_flag));
-        RSR_TRY(rsr::launch_sort(code, nb, cols, h->k, h->base, P, pd.pi, pd.off));
-        RSR_TRY(rsr::launch_stream_len(pd.off, nb, cols, P, lens));
-        RSR_TRY(hipMemcpy(host_lens.data(), lens, (size_t)nb * sizeof(uint32_t),
-                          hipMemcpyDeviceToHost));
-        for (int64_t b = 0; b < nb; ++b)
-            if (host_lens[(size_t)b] > max_len[ps]) max_len[ps] = host_lens[(size_t)b];
+        RSR_TRY(dev_alloc(&h->pass[ps].pi, (size_t)(nb * cols)));
+        RSR_TRY(dev_alloc(&h->pass[ps].off, (size_t)(nb * (P + 1))));
     }
-    RSR_TRY(hipMemcpy(&host_flag, err_flag, sizeof(int), hipMemcpyDeviceToHost));
-    if (host_flag) { rc = RSR_EVALUE; goto done; }
-
+    if ((rc = run_sort_passes(h, M, t, max_len)) != RSR_OK) goto done;
     {
         const int64_t longest = max_len[0] > max_len[1] ? max_len[0] : max_len[1];
         rsr::choose_launch_shape(longest, nb, &h->H, &h->W);
@@ -127,26 +170,20 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
         rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
         RSR_TRY(dev_alloc(&h->fpack, (size_t)h->k * h->fold.G * 64));
         RSR_TRY(dev_alloc(&h->fshare, (size_t)h->W * 64));
-        RSR_TRY(rsr::launch_fold_tables(h->base, h->k, h->fold, h->W, h->fpack, h->fshare));
-        RSR_TRY(dev_alloc(&scratch, (size_t)(nb * maxS)));
+        RSR_TRY(dev_alloc(&t.logical, (size_t)(nb * maxS)));
         for (int ps = 0; ps < h->npass; ++ps) {
             rsr::PassData &pd = h->pass[ps];
             RSR_TRY(dev_alloc(&pd.entries, (size_t)(nb * pd.C * chunk)));
             RSR_TRY(dev_alloc(&pd.codes, (size_t)(nb * pd.C * 64)));
             RSR_TRY(dev_alloc(&pd.wsign, (size_t)(nb * h->W * 16)));
-            RSR_TRY(rsr::launch_pack_stream(pd.pi, pd.off, nb, cols, P, pd.C, h->H, h->enc, scratch,
-                                            pd.entries, pd.codes, err_flag));
-            RSR_TRY(rsr::launch_wave_signs(h->base, h->k, pd.codes, nb, pd.C, h->W, h->fold, ps,
-                                           pd.wsign));
         }
     }
-    RSR_TRY(hipMemcpy(&host_flag, err_flag, sizeof(int), hipMemcpyDeviceToHost));
-    if (host_flag) rc = RSR_EINTERNAL;
+    rc = run_pack_passes(h, t);
 done:
-    if (code) (void)hipFree(code);
-    if (scratch) (void)hipFree(scratch);
-    if (lens) (void)hipFree(lens);
-    if (err_flag) (void)hipFree(err_flag);
+    if (t.code) (void)hipFree(t.code);
+    if (t.logical) (void)hipFree(t.logical);
+    if (t.lens) (void)hipFree(t.lens);
+    if (t.flags) (void)hipFree(t.flags);
     return rc;
 }
 
@@ -292,6 +329,89 @@ rsr_handle_t rsr_preprocess_transposed(const int8_t *M, int64_t rows, int64_t co
 }
 
 int rsr_block_height(rsr_handle_t h) { return good(h) ? h->k : 0; }
+
+}  // extern "C"
+
+// ---- preprocessing without allocation ---------------------------------------------------
+// The temporaries of rsr_preprocess_into live in this fixed array.  Each GPU holds its own
+// copy at its own address; host code must go through the address hipGetSymbolAddress
+// returns for the current device (kept per device below), never through the array's name.
+namespace {
+
+constexpr size_t kStaticScratchBytes = (size_t)RSR_INTO_SCRATCH_BYTES;
+static __device__ __attribute__((used)) __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+std::atomic<unsigned char *> g_scratch_ptr[rsr::kMaxDevices];
+
+// Address of the current device's copy of the scratch array (device must be current).
+int static_scratch(int device, unsigned char **out) {
+    if (device < 0 || device >= rsr::kMaxDevices) return RSR_EHIP;
+    unsigned char *p = g_scratch_ptr[device].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) {
+            (void)hipGetLastError();
+            return RSR_EHIP;
+        }
+        p = static_cast<unsigned char *>(sym);
+        g_scratch_ptr[device].store(p, std::memory_order_release);  // same value from any thread
+    }
+    *out = p;
+    return RSR_OK;
+}
+
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+}  // namespace
+
+extern "C" {
+
+int rsr_preprocess_into(rsr_handle_t h, const int8_t *M) {
+    if (!good(h) || !M) return fail(RSR_EINVAL);
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return fail(RSR_EHIP);
+    if (device != h->device) return fail(RSR_EINVAL);
+    unsigned char *base = nullptr;
+    if (int rc = static_scratch(device, &base)) return fail(rc);
+
+    // carve the temporaries out of the fixed array; refuse what does not fit
+    Temps t;
+    size_t at = 0;
+    t.flags = reinterpret_cast<int *>(base + at);
+    at += align256(kFlagWords * sizeof(int));
+    int rc;
+    if (h->kind == RSR_DENSE_TERNARY_P2) {
+        h->stale = true;
+        rc = run_dense(h, M, t);
+    } else {
+        const int64_t chunk = (int64_t)rsr::kLoad * h->H;
+        int64_t maxS = 0;
+        for (int ps = 0; ps < h->npass; ++ps)
+            if (h->pass[ps].C * chunk > maxS) maxS = h->pass[ps].C * chunk;
+        t.lens = reinterpret_cast<uint32_t *>(base + at);
+        at += align256((size_t)h->nb * sizeof(uint32_t));
+        t.code = reinterpret_cast<uint16_t *>(base + at);
+        at += align256((size_t)(h->nb * h->cols) * sizeof(uint16_t));
+        t.logical = reinterpret_cast<uint16_t *>(base + at);
+        at += align256((size_t)(h->nb * maxS) * sizeof(uint16_t));
+        if (at > kStaticScratchBytes) return fail(RSR_ESCRATCH);
+        h->stale = true;  // from here on the handle's buffers are being rewritten
+        int64_t max_len[2] = {0, 0};
+        rc = run_sort_passes(h, M, t, max_len);
+        for (int ps = 0; rc == RSR_OK && ps < h->npass; ++ps)
+            if (max_len[ps] > h->pass[ps].C * chunk) rc = RSR_EUNSUPPORTED;  // stream outgrew the handle
+        if (rc == RSR_OK) rc = run_pack_passes(h, t);
+    }
+    if (rc == RSR_OK && hipDeviceSynchronize() != hipSuccess) rc = RSR_EHIP;
+    if (rc != RSR_OK) {
+        (void)hipGetLastError();
+        return fail(rc);
+    }
+    h->stale = false;
+    g_last_error = RSR_OK;
+    return RSR_OK;
+}
+
 
 // ---- a handle as bytes --------------------------------------------------------------------
 }  // extern "C"
@@ -443,6 +563,7 @@ int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void 
                   int64_t ldv, int64_t ldo, void *stream) {
     if (!good(h) || !v || !out || batch < 1 || (v_dtype != RSR_F32 && v_dtype != RSR_BF16))
         return fail(RSR_EINVAL);
+    if (h->stale) return fail(RSR_EINVAL);  // a failed rsr_preprocess_into left it half-written
     if (batch > 65535) return fail(RSR_EUNSUPPORTED);
     if (batch > 1 && (ldv < h->cols || ldo < h->rows)) return fail(RSR_EINVAL);
     int device = -1;
@@ -478,6 +599,7 @@ const char *rsr_error_string(int code) {
         case RSR_ENOMEM: return "out of memory";
         case RSR_EHIP: return "HIP runtime error";
         case RSR_EINTERNAL: return "preprocessing self-check failed";
+        case RSR_ESCRATCH: return "input needs more temporary memory than the fixed scratch of rsr_preprocess_into";
         default: return "unknown error";
     }
 }

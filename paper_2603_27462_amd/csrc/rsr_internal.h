@@ -61,6 +61,7 @@ struct rsr_handle_s {
     rsr::FoldShape fold;
     uint32_t *fpack = nullptr;   // scatter-phase weights, four per dword: [k][fold.G][64]
     uint32_t *fshare = nullptr;  // first entry of the level-1 share of every thread [W*64]
+    bool stale = false;          // a failed rsr_preprocess_into left the buffers half-written
     uint8_t *packed = nullptr;   // dense kind: [rows/16][tiles][64 lanes][16 bytes], row_bytes = 64 tiles
     int64_t row_bytes = 0;
 };
@@ -83,7 +84,8 @@ hipError_t launch_encode(const int8_t *M, int64_t rows, int64_t cols, int k, int
 hipError_t launch_sort(const uint16_t *code, int64_t nb, int64_t cols, int k, int base, int64_t P,
                        uint16_t *pi, uint32_t *off);
 hipError_t launch_stream_len(const uint32_t *off, int64_t nb, int64_t cols, int64_t P,
-                             uint32_t *lens);
+                             uint32_t *lens, uint32_t *longest);
+hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t count);
 hipError_t launch_pack_stream(const uint16_t *pi, const uint32_t *off, int64_t nb, int64_t cols,
                               int64_t P, int64_t C, int H, int enc, uint16_t *scratch,
                               uint16_t *entries, uint16_t *codes, int *err_flag);

@@ -152,10 +152,12 @@ __global__ __launch_bounds__(kThreads) void k_sort(const uint16_t *__restrict__ 
 }
 
 // lens[b] = stream entries of block b: columns outside group 0 plus one
-// placeholder for every empty group among codes 1..P-1.
+// placeholder for every empty group among codes 1..P-1; *longest = max over blocks
+// (the caller zeroes it).
 __global__ __launch_bounds__(kThreads) void k_stream_len(const uint32_t *__restrict__ off,
                                                          int64_t nb, int64_t n, int64_t P,
-                                                         uint32_t *__restrict__ lens) {
+                                                         uint32_t *__restrict__ lens,
+                                                         uint32_t *__restrict__ longest) {
     __shared__ uint32_t empties;
     for (int64_t b = blockIdx.x; b < nb; b += gridDim.x) {
         const uint32_t *ob = off + b * (P + 1);
@@ -165,7 +167,11 @@ __global__ __launch_bounds__(kThreads) void k_stream_len(const uint32_t *__restr
         for (int64_t c = 1 + threadIdx.x; c < P; c += kThreads) mine += (ob[c + 1] == ob[c]);
         if (mine) atomicAdd(&empties, mine);
         __syncthreads();
-        if (threadIdx.x == 0) lens[b] = (uint32_t)(n - ob[1]) + empties;
+        if (threadIdx.x == 0) {
+            const uint32_t len = (uint32_t)(n - ob[1]) + empties;
+            lens[b] = len;
+            atomicMax(longest, len);
+        }
         __syncthreads();
     }
 }
@@ -317,6 +323,13 @@ __global__ __launch_bounds__(kThreads) void k_finalize_stream(
     }
 }
 
+// Plain fill (used instead of a memset node so that callers may capture the sequence).
+__global__ __launch_bounds__(kThreads) void k_fill_u32(uint32_t *__restrict__ p, uint32_t value,
+                                                       int64_t count) {
+    const int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (i < count) p[i] = value;
+}
+
 int grid_for_blocks(int64_t nb) { return (int)(nb < 4096 ? nb : 4096); }
 
 // T[j][i] = M[i][j] through 64 x 64 tiles in LDS (coalesced on both sides).
@@ -380,9 +393,15 @@ hipError_t launch_transpose(const int8_t *M, int64_t rows, int64_t cols, int8_t 
 }
 
 hipError_t launch_stream_len(const uint32_t *off, int64_t nb, int64_t cols, int64_t P,
-                             uint32_t *lens) {
+                             uint32_t *lens, uint32_t *longest) {
     hipLaunchKernelGGL(k_stream_len, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, off, nb,
-                       cols, P, lens);
+                       cols, P, lens, longest);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t count) {
+    hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)((count + kThreads - 1) / kThreads)), dim3(kThreads),
+                       0, 0, p, value, count);
     return hipGetLastError();
 }
 

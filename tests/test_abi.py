@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_error_strings_without_gpu():
     assert rsr.rsr_error_string(0) == "ok"
-    for code in range(1, 7):
+    for code in range(1, 8):
         assert rsr.rsr_error_string(code) not in ("ok", "unknown error")
     assert rsr.rsr_error_string(99) == "unknown error"
 
