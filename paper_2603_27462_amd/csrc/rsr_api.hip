@@ -33,8 +33,10 @@ void free_handle(rsr_handle_s *h) {
         if (ps.pi) (void)hipFree(ps.pi);
         if (ps.off) (void)hipFree(ps.off);
         if (ps.entries) (void)hipFree(ps.entries);
-        if (ps.codes) (void)hipFree(ps.codes);
-        if (ps.wsign) (void)hipFree(ps.wsign);
+        if (ps.start) (void)hipFree(ps.start);
+        if (ps.sgn) (void)hipFree(ps.sgn);
+        if (ps.gword) (void)hipFree(ps.gword);
+        if (ps.gcount) (void)hipFree(ps.gcount);
     }
     if (h->fpack) (void)hipFree(h->fpack);
     if (h->fshare) (void)hipFree(h->fshare);
@@ -59,16 +61,22 @@ int hip_code(hipError_t e) { return e == hipErrorOutOfMemory ? RSR_ENOMEM : RSR_
     } while (0)
 
 // Device memory a preprocessing run needs besides the handle's own buffers: the pattern
-// codes of every (block, column), the stream in logical order, one length per block, and
-// a few words of flags (kFlagErr: entry outside the alphabet / self-check; kFlagLen + pass:
-// longest stream of a block).
+// codes of every (block, column), the stream in logical order, the codes of the non-empty
+// groups (rank-indexed handles), and a few words of flags (kFlagErr: entry outside the
+// alphabet / self-check; kFlagStats + 3 * pass: the three maxima of launch_stream_stats).
 struct Temps {
     uint16_t *code = nullptr;     // [nb][cols]
-    uint16_t *logical = nullptr;  // [nb][max over passes of C * chunk]
-    uint32_t *lens = nullptr;     // [nb]
+    uint16_t *logical = nullptr;  // [nb][max over passes of S * 512]
+    uint16_t *gcode = nullptr;    // [nb][slots], rank-indexed handles only
     int *flags = nullptr;         // [kFlagWords]
 };
-constexpr int kFlagErr = 0, kFlagLen = 1, kFlagWords = 64;
+constexpr int kFlagErr = 0, kFlagStats = 1, kFlagWords = 64;
+
+// What the streams of a matrix need, per pass: longest stream of a block without and with
+// placeholders for empty groups, and the most non-empty groups of a block.
+struct StreamStats {
+    int64_t real[2] = {0, 0}, with_empty[2] = {0, 0}, groups[2] = {0, 0};
+};
 
 int read_flags(const Temps &t, int (&host)[kFlagWords]) {
     return hipMemcpy(host, t.flags, sizeof(host), hipMemcpyDeviceToHost) == hipSuccess ? RSR_OK
@@ -84,8 +92,8 @@ int run_dense(rsr_handle_s *h, const int8_t *M, const Temps &t) {
     return host[kFlagErr] ? RSR_EVALUE : RSR_OK;
 }
 
-// encode -> counting sort -> stream length, per pass; max_len[ps] = longest stream of a block
-int run_sort_passes(rsr_handle_s *h, const int8_t *M, const Temps &t, int64_t (&max_len)[2]) {
+// encode -> counting sort -> stream statistics, per pass
+int run_sort_passes(rsr_handle_s *h, const int8_t *M, const Temps &t, StreamStats *st) {
     static const int modes[3][2] = {{rsr::MODE_BINARY, 0}, {rsr::MODE_POS, rsr::MODE_NEG},
                                     {rsr::MODE_FUSED3, 0}};
     int host[kFlagWords];
@@ -97,32 +105,43 @@ int run_sort_passes(rsr_handle_s *h, const int8_t *M, const Temps &t, int64_t (&
         if (rsr::launch_encode(M, h->rows, h->cols, h->k, modes[h->kind][ps], t.code,
                                t.flags + kFlagErr) != hipSuccess ||
             rsr::launch_sort(t.code, h->nb, h->cols, h->k, h->base, h->P, pd.pi, pd.off) != hipSuccess ||
-            rsr::launch_stream_len(pd.off, h->nb, h->cols, h->P, t.lens,
-                                   reinterpret_cast<uint32_t *>(t.flags + kFlagLen + ps)) != hipSuccess)
+            rsr::launch_stream_stats(pd.off, h->nb, h->cols, h->P,
+                                     reinterpret_cast<uint32_t *>(t.flags + kFlagStats + 3 * ps)) !=
+                hipSuccess)
             return RSR_EHIP;
     }
     if (int rc = read_flags(t, host)) return rc;
     if (host[kFlagErr]) return RSR_EVALUE;
-    max_len[0] = (uint32_t)host[kFlagLen];
-    max_len[1] = (uint32_t)host[kFlagLen + 1];
+    for (int ps = 0; ps < h->npass; ++ps) {
+        st->real[ps] = (uint32_t)host[kFlagStats + 3 * ps];
+        st->with_empty[ps] = (uint32_t)host[kFlagStats + 3 * ps + 1];
+        st->groups[ps] = (uint32_t)host[kFlagStats + 3 * ps + 2];
+    }
     return RSR_OK;
+}
+
+int64_t slabs_for(int64_t entries) {
+    const int64_t s = (entries + rsr::kSlab - 1) / rsr::kSlab;
+    return s < 1 ? 1 : s;
 }
 
 // the stream and the small tables of the multiply kernel, in the layout the handle records
 int run_pack_passes(rsr_handle_s *h, const Temps &t) {
     int host[kFlagWords];
-    if (rsr::launch_fold_tables(h->base, h->k, h->fold, h->W, h->fpack, h->fshare) != hipSuccess)
+    if (!h->by_rank &&
+        rsr::launch_fold_tables(h->base, h->k, h->fold, h->W, h->fpack, h->fshare) != hipSuccess)
         return RSR_EHIP;
-    for (int ps = 0; ps < h->npass; ++ps) {
-        rsr::PassData &pd = h->pass[ps];
-        if (rsr::launch_pack_stream(pd.pi, pd.off, h->nb, h->cols, h->P, pd.C, h->H, h->enc, t.logical,
-                                    pd.entries, pd.codes, t.flags + kFlagErr) != hipSuccess ||
-            rsr::launch_wave_signs(h->base, h->k, pd.codes, h->nb, pd.C, h->W, h->fold, ps,
-                                   pd.wsign) != hipSuccess)
+    for (int ps = 0; ps < h->npass; ++ps)
+        if (rsr::launch_pack_pass(h, ps, t.logical, t.gcode, t.flags + kFlagErr) != hipSuccess)
             return RSR_EHIP;
-    }
     if (int rc = read_flags(t, host)) return rc;
     return host[kFlagErr] ? RSR_EINTERNAL : RSR_OK;
+}
+
+// Bytes of the strip-sign table of one pass.
+size_t sign_table_bytes(const rsr_handle_s *h) {
+    if (h->by_rank) return (size_t)h->nb * h->W * 64 * 4;
+    return (size_t)h->nb * h->k * 64 * (h->W <= 8 ? 2 : 4);
 }
 
 int preprocess_dense(rsr_handle_s *h, const int8_t *M) {
@@ -144,45 +163,56 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
     int rc = RSR_OK;
     Temps t;
     const int64_t nb = h->nb, cols = h->cols, P = h->P;
-    int64_t max_len[2] = {0, 0};
+    StreamStats st;
 
     RSR_TRY(dev_alloc(&t.code, (size_t)(nb * cols)));
-    RSR_TRY(dev_alloc(&t.lens, (size_t)nb));
     RSR_TRY(dev_alloc(&t.flags, kFlagWords));
     for (int ps = 0; ps < h->npass; ++ps) {
         RSR_TRY(dev_alloc(&h->pass[ps].pi, (size_t)(nb * cols)));
         RSR_TRY(dev_alloc(&h->pass[ps].off, (size_t)(nb * (P + 1))));
     }
-    if ((rc = run_sort_passes(h, M, t, max_len)) != RSR_OK) goto done;
+    if ((rc = run_sort_passes(h, M, t, &st)) != RSR_OK) goto done;
     {
-        const int64_t longest = max_len[0] > max_len[1] ? max_len[0] : max_len[1];
-        rsr::choose_launch_shape(longest, nb, &h->H, &h->W);
-        h->enc = (cols <= rsr::kSmallCols) ? rsr::kEncSmall : rsr::kEncBig;
-        const int64_t chunk = (int64_t)rsr::kLoad * h->H;
-        int64_t maxS = 0;
+        const int ph = (h->npass == 2 && st.with_empty[1] > st.with_empty[0]) ? 1 : 0;  // the heavier pass
+        h->by_rank = rsr::choose_by_rank(P, cols, st.with_empty[ph], st.real[ph], st.groups[ph]) ? 1 : 0;
+        int64_t maxS = 0, most = 0;
         for (int ps = 0; ps < h->npass; ++ps) {
             rsr::PassData &pd = h->pass[ps];
-            pd.C = (max_len[ps] + chunk - 1) / chunk;
-            if (pd.C < 1) pd.C = 1;
-            if (pd.C * chunk > maxS) maxS = pd.C * chunk;
+            pd.S = slabs_for(h->by_rank ? st.real[ps] : st.with_empty[ps]);
+            if (pd.S > maxS) maxS = pd.S;
+            if (st.groups[ps] > most) most = st.groups[ps];
         }
-        const int64_t chunks[2] = {h->pass[0].C, h->pass[1].C};
-        rsr::make_fold_shape(h->base, h->k, P, h->W, chunks, h->npass, &h->fold);
-        RSR_TRY(dev_alloc(&h->fpack, (size_t)h->k * h->fold.G * 64));
-        RSR_TRY(dev_alloc(&h->fshare, (size_t)h->W * 64));
-        RSR_TRY(dev_alloc(&t.logical, (size_t)(nb * maxS)));
+        h->slots = h->by_rank ? most + 1 : P;
+        h->W = rsr::choose_waves(maxS, nb);
+        h->enc = (cols <= rsr::kSmallCols) ? rsr::kEncSmall : rsr::kEncBig;
+        if (rsr::matvec_lds_bytes(h->slots, cols, 4, h->W, h->by_rank != 0) > rsr::kLdsBytes) {
+            rc = RSR_EUNSUPPORTED;
+            goto done;
+        }
+        if (h->by_rank) {
+            RSR_TRY(dev_alloc(&t.gcode, (size_t)(nb * h->slots)));
+        } else {
+            rsr::make_fold_shape(h->base, h->k, P, h->W, &h->fold);
+            RSR_TRY(dev_alloc(&h->fpack, (size_t)h->k * h->fold.G * 64));
+            RSR_TRY(dev_alloc(&h->fshare, (size_t)h->W * 64));
+        }
+        RSR_TRY(dev_alloc(&t.logical, (size_t)(nb * maxS * rsr::kSlab)));
         for (int ps = 0; ps < h->npass; ++ps) {
             rsr::PassData &pd = h->pass[ps];
-            RSR_TRY(dev_alloc(&pd.entries, (size_t)(nb * pd.C * chunk)));
-            RSR_TRY(dev_alloc(&pd.codes, (size_t)(nb * pd.C * 64)));
-            RSR_TRY(dev_alloc(&pd.wsign, (size_t)(nb * h->W * 16)));
+            RSR_TRY(dev_alloc(&pd.entries, (size_t)(nb * pd.S * rsr::kSlab)));
+            RSR_TRY(dev_alloc(&pd.start, (size_t)(nb * h->W * 64)));
+            RSR_TRY(dev_alloc(reinterpret_cast<unsigned char **>(&pd.sgn), sign_table_bytes(h)));
+            if (h->by_rank) {
+                RSR_TRY(dev_alloc(&pd.gword, (size_t)(nb * h->slots)));
+                RSR_TRY(dev_alloc(&pd.gcount, (size_t)nb));
+            }
         }
     }
     rc = run_pack_passes(h, t);
 done:
     if (t.code) (void)hipFree(t.code);
     if (t.logical) (void)hipFree(t.logical);
-    if (t.lens) (void)hipFree(t.lens);
+    if (t.gcode) (void)hipFree(t.gcode);
     if (t.flags) (void)hipFree(t.flags);
     return rc;
 }
@@ -213,11 +243,6 @@ rsr_handle_s *preprocess_with_k(const int8_t *M, int64_t rows, int64_t cols, int
         if (k > kmax) { free_handle(h); fail(RSR_EUNSUPPORTED); return nullptr; }
         h->P = ipow(h->base, k);
         h->nb = (rows + k - 1) / k;
-        if (rsr::matvec_lds_bytes(h->P, cols, 4, rsr::kMaxWaves) > rsr::kLdsBytes) {
-            free_handle(h);
-            fail(RSR_EUNSUPPORTED);
-            return nullptr;
-        }
         rc = preprocess_rsr(h, M);
     }
     if (rc == RSR_OK && hipDeviceSynchronize() != hipSuccess) rc = RSR_EHIP;
@@ -384,22 +409,27 @@ int rsr_preprocess_into(rsr_handle_t h, const int8_t *M) {
         h->stale = true;
         rc = run_dense(h, M, t);
     } else {
-        const int64_t chunk = (int64_t)rsr::kLoad * h->H;
         int64_t maxS = 0;
         for (int ps = 0; ps < h->npass; ++ps)
-            if (h->pass[ps].C * chunk > maxS) maxS = h->pass[ps].C * chunk;
-        t.lens = reinterpret_cast<uint32_t *>(base + at);
-        at += align256((size_t)h->nb * sizeof(uint32_t));
+            if (h->pass[ps].S > maxS) maxS = h->pass[ps].S;
         t.code = reinterpret_cast<uint16_t *>(base + at);
         at += align256((size_t)(h->nb * h->cols) * sizeof(uint16_t));
         t.logical = reinterpret_cast<uint16_t *>(base + at);
-        at += align256((size_t)(h->nb * maxS) * sizeof(uint16_t));
+        at += align256((size_t)(h->nb * maxS * rsr::kSlab) * sizeof(uint16_t));
+        if (h->by_rank) {
+            t.gcode = reinterpret_cast<uint16_t *>(base + at);
+            at += align256((size_t)(h->nb * h->slots) * sizeof(uint16_t));
+        }
         if (at > kStaticScratchBytes) return fail(RSR_ESCRATCH);
         h->stale = true;  // from here on the handle's buffers are being rewritten
-        int64_t max_len[2] = {0, 0};
-        rc = run_sort_passes(h, M, t, max_len);
-        for (int ps = 0; rc == RSR_OK && ps < h->npass; ++ps)
-            if (max_len[ps] > h->pass[ps].C * chunk) rc = RSR_EUNSUPPORTED;  // stream outgrew the handle
+        StreamStats st;
+        rc = run_sort_passes(h, M, t, &st);
+        for (int ps = 0; rc == RSR_OK && ps < h->npass; ++ps) {
+            // the new matrix has to fit the layout the handle was allocated for
+            const int64_t need = h->by_rank ? st.real[ps] : st.with_empty[ps];
+            if (need > h->pass[ps].S * rsr::kSlab || (h->by_rank && st.groups[ps] + 1 > h->slots))
+                rc = RSR_EUNSUPPORTED;
+        }
         if (rc == RSR_OK) rc = run_pack_passes(h, t);
     }
     if (rc == RSR_OK && hipDeviceSynchronize() != hipSuccess) rc = RSR_EHIP;
@@ -419,13 +449,14 @@ int rsr_preprocess_into(rsr_handle_t h, const int8_t *M) {
 namespace {
 
 constexpr uint32_t kSerialMagic = 0x53525352u;  // "RSRS"
-constexpr uint32_t kSerialVersion = 1;
+constexpr uint32_t kSerialVersion = 2;
 
 struct SerialHeader {
     uint32_t magic, version;
-    int32_t kind, k, base, npass, W, H, enc, reserved;
+    int32_t kind, k, base, npass, W, by_rank, enc, reserved;
     int64_t rows, cols, nb, P, row_bytes;
-    int64_t C[2];
+    int64_t S[2];
+    int64_t slots;
     float sign[2];
     int64_t total_bytes;  // header + buffers
 };
@@ -447,12 +478,18 @@ std::vector<Piece> pieces_of(rsr_handle_s *h) {
         rsr::PassData &pd = h->pass[ps];
         p.push_back({reinterpret_cast<void **>(&pd.pi), (size_t)(h->nb * h->cols) * 2});
         p.push_back({reinterpret_cast<void **>(&pd.off), (size_t)(h->nb * (h->P + 1)) * 4});
-        p.push_back({reinterpret_cast<void **>(&pd.entries), (size_t)(h->nb * pd.C * rsr::kLoad * h->H) * 2});
-        p.push_back({reinterpret_cast<void **>(&pd.codes), (size_t)(h->nb * pd.C * 64) * 2});
-        p.push_back({reinterpret_cast<void **>(&pd.wsign), (size_t)(h->nb * h->W * 16)});
+        p.push_back({reinterpret_cast<void **>(&pd.entries), (size_t)(h->nb * pd.S * rsr::kSlab) * 2});
+        p.push_back({reinterpret_cast<void **>(&pd.start), (size_t)(h->nb * h->W * 64) * 2});
+        p.push_back({&pd.sgn, sign_table_bytes(h)});
+        if (h->by_rank) {
+            p.push_back({reinterpret_cast<void **>(&pd.gword), (size_t)(h->nb * h->slots) * 4});
+            p.push_back({reinterpret_cast<void **>(&pd.gcount), (size_t)h->nb * 4});
+        }
     }
-    p.push_back({reinterpret_cast<void **>(&h->fpack), (size_t)h->k * h->fold.G * 64 * 4});
-    p.push_back({reinterpret_cast<void **>(&h->fshare), (size_t)h->W * 64 * 4});
+    if (!h->by_rank) {
+        p.push_back({reinterpret_cast<void **>(&h->fpack), (size_t)h->k * h->fold.G * 64 * 4});
+        p.push_back({reinterpret_cast<void **>(&h->fshare), (size_t)h->W * 64 * 4});
+    }
     return p;
 }
 
@@ -476,9 +513,9 @@ int rsr_serialize(rsr_handle_t h, void *host_buf, int64_t capacity) {
     hd.magic = kSerialMagic;
     hd.version = kSerialVersion;
     hd.kind = h->kind; hd.k = h->k; hd.base = h->base; hd.npass = h->npass;
-    hd.W = h->W; hd.H = h->H; hd.enc = h->enc;
+    hd.W = h->W; hd.by_rank = h->by_rank; hd.enc = h->enc; hd.slots = h->slots;
     hd.rows = h->rows; hd.cols = h->cols; hd.nb = h->nb; hd.P = h->P; hd.row_bytes = h->row_bytes;
-    for (int ps = 0; ps < 2; ++ps) { hd.C[ps] = h->pass[ps].C; hd.sign[ps] = h->pass[ps].sign; }
+    for (int ps = 0; ps < 2; ++ps) { hd.S[ps] = h->pass[ps].S; hd.sign[ps] = h->pass[ps].sign; }
     hd.total_bytes = total;
     unsigned char *out = static_cast<unsigned char *>(host_buf);
     std::memcpy(out, &hd, sizeof(hd));
@@ -513,13 +550,16 @@ rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size) {
         const bool fused = hd.kind == RSR_TERNARY_FUSED;
         ok = hd.k >= 1 && hd.k <= (fused ? 10 : 15) && hd.base == (fused ? 3 : 2) &&
              hd.npass == (hd.kind == RSR_TERNARY_2PASS ? 2 : 1) && hd.W >= 1 && hd.W <= rsr::kMaxWaves &&
-             (hd.H == 1 || hd.H == 2 || hd.H == 4) &&
+             (hd.by_rank == 0 || hd.by_rank == 1) &&
              hd.enc == (hd.cols <= rsr::kSmallCols ? rsr::kEncSmall : rsr::kEncBig);
         if (ok) {
+            // slots: P by code; by rank at most one per column (every slot owns a tail entry),
+            // and the kernel addresses LDS with it, so it has to fit
             ok = hd.P == ipow(hd.base, hd.k) && hd.nb == (hd.rows + hd.k - 1) / hd.k &&
-                 rsr::matvec_lds_bytes(hd.P, hd.cols, 4, rsr::kMaxWaves) <= rsr::kLdsBytes;
+                 (hd.by_rank ? (hd.slots >= 1 && hd.slots <= hd.cols + 1) : hd.slots == hd.P) &&
+                 rsr::matvec_lds_bytes(hd.slots, hd.cols, 4, hd.W, hd.by_rank != 0) <= rsr::kLdsBytes;
             for (int ps = 0; ok && ps < hd.npass; ++ps)
-                ok = hd.C[ps] >= 1 && hd.C[ps] * rsr::kLoad * hd.H <= 4 * (hd.cols + hd.P) + rsr::kLoad * hd.H;
+                ok = hd.S[ps] >= 1 && hd.S[ps] * rsr::kSlab <= hd.cols + hd.P + rsr::kSlab;
         }
     }
     if (!ok) { fail(RSR_EINVAL); return nullptr; }
@@ -528,13 +568,10 @@ rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size) {
     if (!h) { fail(RSR_ENOMEM); return nullptr; }
     h->magic = rsr::kMagic;
     h->kind = hd.kind; h->k = hd.k; h->base = hd.base; h->npass = hd.npass;
-    h->W = hd.W; h->H = hd.H; h->enc = hd.enc;
+    h->W = hd.W; h->by_rank = hd.by_rank; h->enc = hd.enc; h->slots = hd.slots;
     h->rows = hd.rows; h->cols = hd.cols; h->nb = hd.nb; h->P = hd.P; h->row_bytes = hd.row_bytes;
-    for (int ps = 0; ps < 2; ++ps) { h->pass[ps].C = hd.C[ps]; h->pass[ps].sign = hd.sign[ps]; }
-    if (!dense) {
-        const int64_t chunks[2] = {hd.C[0], hd.C[1]};
-        rsr::make_fold_shape(h->base, h->k, h->P, h->W, chunks, h->npass, &h->fold);
-    }
+    for (int ps = 0; ps < 2; ++ps) { h->pass[ps].S = hd.S[ps]; h->pass[ps].sign = hd.sign[ps]; }
+    if (!dense && !h->by_rank) rsr::make_fold_shape(h->base, h->k, h->P, h->W, &h->fold);
     int rc = RSR_OK;
     if (hipGetDevice(&h->device) != hipSuccess) rc = RSR_EHIP;
     const std::vector<Piece> pieces = pieces_of(h);
@@ -668,9 +705,10 @@ int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch) {
     } else {
         weight_side = 0;
         for (int ps = 0; ps < h->npass; ++ps)
-            weight_side += h->nb * (h->pass[ps].C * ((int64_t)rsr::kLoad * h->H * 2 + 64 * 2) +
-                                    (int64_t)h->W * 16);
-        weight_side += (int64_t)h->k * h->fold.G * 256 + (int64_t)h->W * 64 * 4;
+            weight_side += h->nb * (h->pass[ps].S * (int64_t)rsr::kSlab * 2 + (int64_t)h->W * 64 * 2 +
+                                    (h->by_rank ? h->slots * 4 + 4 : 0)) +
+                           (int64_t)sign_table_bytes(h);
+        if (!h->by_rank) weight_side += (int64_t)h->k * h->fold.G * 256 + (int64_t)h->W * 64 * 4;
     }
     return weight_side + (int64_t)batch * (h->cols * vb + h->rows * 4);
 }
@@ -680,8 +718,10 @@ const char *rsr_kernel_name(rsr_handle_t h, int v_dtype) {
         fail(RSR_EINVAL);
         return nullptr;
     }
-    return h->kind == RSR_DENSE_TERNARY_P2 ? rsr::dense_matvec_kernel_name(h, v_dtype)
-                                           : rsr::rsr_matvec_kernel_name(v_dtype, h->H, h->enc, h->npass, rsr::matvec_is_single(h));
+    if (h->kind == RSR_DENSE_TERNARY_P2) return rsr::dense_matvec_kernel_name(h, v_dtype);
+    static thread_local char name[96];
+    rsr::rsr_matvec_kernel_name(h, v_dtype, name, sizeof(name));
+    return name;
 }
 
 }  // extern "C"

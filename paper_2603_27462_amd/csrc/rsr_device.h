@@ -41,14 +41,10 @@ __device__ __forceinline__ float wave_inclusive_scan(float x) {
     return x;
 }
 
-// Value of lane l-1 (0 in lane 0).
-__device__ __forceinline__ float wave_shift_right(float x) {
-    return __int_as_float(
-        __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x138 /* wave_shr:1 */, 0xf, 0xf, false));
-}
-
-__device__ __forceinline__ float lane63(float x) {
-    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+// Signed bit field of `width` bits at bit `at`.
+__device__ __forceinline__ float field_as_float(uint32_t word, int at, int width) {
+    // (the builtin is declared unsigned: the cast back to int keeps the sign)
+    return (float)(int)__builtin_amdgcn_sbfe((int)word, (unsigned)at, (unsigned)width);
 }
 
 // ---- the per-entry steps, written out as instructions --------------------------------
@@ -88,60 +84,37 @@ __device__ __forceinline__ void lds_wait(uint32_t (&g)[8]) {
                  : "n"(N));
 }
 
-// The two entries of dword d: if an entry is a tail, E[ptr] = base + s, ptr += 4.
+// The two entries of dword d: if an entry is a tail, E[ptr] = s, ptr += 4.
 // The compare writes the execution mask itself (all 64 lanes are live when this runs:
 // the workgroup size is a multiple of 64 and the caller is in wave-uniform control
-// flow), and the mask is set back to all ones afterwards.  Small encoding: the tail
-// flag is the sign of the 16-bit entry (low half: 16-bit compare; high half: sign of
-// the dword).  Big encoding: bit 0 / bit 16, moved to the sign by a shift.
-template <int ENC>
-__device__ __forceinline__ void tail_store2(uint32_t d, float base, float s0, float s1,
-                                            uint32_t &ptr) {
-    float t;
-    if (ENC == kEncSmall) {
-        asm volatile(
-            "v_cmpx_gt_i16 vcc, 0, %[d]\n\t"
-            "v_add_f32 %[t], %[b], %[s0]\n\t"
-            "ds_write_b32 %[p], %[t]\n\t"
-            "v_add_u32 %[p], 4, %[p]\n\t"
-            "s_mov_b64 exec, -1\n\t"
-            "v_cmpx_gt_i32 vcc, 0, %[d]\n\t"
-            "v_add_f32 %[t], %[b], %[s1]\n\t"
-            "ds_write_b32 %[p], %[t]\n\t"
-            "v_add_u32 %[p], 4, %[p]\n\t"
-            "s_mov_b64 exec, -1"
-            : [p] "+v"(ptr), [t] "=&v"(t)
-            : [d] "v"(d), [b] "v"(base), [s0] "v"(s0), [s1] "v"(s1)
-            : "vcc", "memory");
-    } else {
-        uint32_t u;
-        asm volatile(
-            "v_lshlrev_b32 %[u], 31, %[d]\n\t"
-            "v_cmpx_gt_i32 vcc, 0, %[u]\n\t"
-            "v_add_f32 %[t], %[b], %[s0]\n\t"
-            "ds_write_b32 %[p], %[t]\n\t"
-            "v_add_u32 %[p], 4, %[p]\n\t"
-            "s_mov_b64 exec, -1\n\t"
-            "v_lshlrev_b32 %[u], 15, %[d]\n\t"
-            "v_cmpx_gt_i32 vcc, 0, %[u]\n\t"
-            "v_add_f32 %[t], %[b], %[s1]\n\t"
-            "ds_write_b32 %[p], %[t]\n\t"
-            "v_add_u32 %[p], 4, %[p]\n\t"
-            "s_mov_b64 exec, -1"
-            : [p] "+v"(ptr), [t] "=&v"(t), [u] "=&v"(u)
-            : [d] "v"(d), [b] "v"(base), [s0] "v"(s0), [s1] "v"(s1)
-            : "vcc", "memory");
-    }
+// flow), and the mask is set back to all ones afterwards.  Big encoding: the tail flag
+// is bit 0 / bit 16, moved to the sign by a shift.
+__device__ __forceinline__ void tail_store2_big(uint32_t d, float s0, float s1, uint32_t &ptr) {
+    uint32_t u;
+    asm volatile(
+        "v_lshlrev_b32 %[u], 31, %[d]\n\t"
+        "v_cmpx_gt_i32 vcc, 0, %[u]\n\t"
+        "ds_write_b32 %[p], %[s0]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, -1\n\t"
+        "v_lshlrev_b32 %[u], 15, %[d]\n\t"
+        "v_cmpx_gt_i32 vcc, 0, %[u]\n\t"
+        "ds_write_b32 %[p], %[s1]\n\t"
+        "v_add_u32 %[p], 4, %[p]\n\t"
+        "s_mov_b64 exec, -1"
+        : [p] "+v"(ptr), [u] "=&v"(u)
+        : [d] "v"(d), [s0] "v"(s0), [s1] "v"(s1)
+        : "vcc", "memory");
 }
 
-// Eight entries (dwords d0..d3) at once, small encoding: the eight tail masks and the eight
-// sums base + s are computed first, as independent instructions, so that the part that has
-// to run in order -- set the execution mask, store, advance the pointer -- is three
-// instructions per entry with a single vector instruction in the dependency chain.
+// Eight entries (dwords d0..d3) at once, small encoding (the tail flag is the sign of the
+// 16-bit entry: a 16-bit compare for the low half, the sign of the dword for the high
+// half): the eight tail masks are computed first, as independent instructions, so that the
+// part that has to run in order -- set the execution mask, store, advance the pointer --
+// is three instructions per entry with a single vector instruction in the dependency chain.
 __device__ __forceinline__ void tail_store8_small(uint32_t d0, uint32_t d1, uint32_t d2, uint32_t d3,
-                                                  float base, const float (&s)[8], uint32_t &ptr) {
+                                                  const float (&s)[8], uint32_t &ptr) {
     uint64_t m0, m1, m2, m3, m4, m5, m6, m7;
-    float t0, t1, t2, t3, t4, t5, t6, t7;
     asm volatile(
         "v_cmp_gt_i16 %[m0], 0, %[d0]\n\t"
         "v_cmp_gt_i32 %[m1], 0, %[d0]\n\t"
@@ -151,44 +124,34 @@ __device__ __forceinline__ void tail_store8_small(uint32_t d0, uint32_t d1, uint
         "v_cmp_gt_i32 %[m5], 0, %[d2]\n\t"
         "v_cmp_gt_i16 %[m6], 0, %[d3]\n\t"
         "v_cmp_gt_i32 %[m7], 0, %[d3]\n\t"
-        "v_add_f32 %[t0], %[b], %[s0]\n\t"
-        "v_add_f32 %[t1], %[b], %[s1]\n\t"
-        "v_add_f32 %[t2], %[b], %[s2]\n\t"
-        "v_add_f32 %[t3], %[b], %[s3]\n\t"
-        "v_add_f32 %[t4], %[b], %[s4]\n\t"
-        "v_add_f32 %[t5], %[b], %[s5]\n\t"
-        "v_add_f32 %[t6], %[b], %[s6]\n\t"
-        "v_add_f32 %[t7], %[b], %[s7]\n\t"
         "s_mov_b64 exec, %[m0]\n\t"
-        "ds_write_b32 %[p], %[t0]\n\t"
+        "ds_write_b32 %[p], %[s0]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, %[m1]\n\t"
-        "ds_write_b32 %[p], %[t1]\n\t"
+        "ds_write_b32 %[p], %[s1]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, %[m2]\n\t"
-        "ds_write_b32 %[p], %[t2]\n\t"
+        "ds_write_b32 %[p], %[s2]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, %[m3]\n\t"
-        "ds_write_b32 %[p], %[t3]\n\t"
+        "ds_write_b32 %[p], %[s3]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, %[m4]\n\t"
-        "ds_write_b32 %[p], %[t4]\n\t"
+        "ds_write_b32 %[p], %[s4]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, %[m5]\n\t"
-        "ds_write_b32 %[p], %[t5]\n\t"
+        "ds_write_b32 %[p], %[s5]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, %[m6]\n\t"
-        "ds_write_b32 %[p], %[t6]\n\t"
+        "ds_write_b32 %[p], %[s6]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, %[m7]\n\t"
-        "ds_write_b32 %[p], %[t7]\n\t"
+        "ds_write_b32 %[p], %[s7]\n\t"
         "v_add_u32 %[p], 4, %[p]\n\t"
         "s_mov_b64 exec, -1"
-        : [p] "+v"(ptr), [t0] "=&v"(t0), [t1] "=&v"(t1), [t2] "=&v"(t2), [t3] "=&v"(t3),
-          [t4] "=&v"(t4), [t5] "=&v"(t5), [t6] "=&v"(t6), [t7] "=&v"(t7), [m0] "=&s"(m0),
-          [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3), [m4] "=&s"(m4), [m5] "=&s"(m5),
-          [m6] "=&s"(m6), [m7] "=&s"(m7)
-        : [d0] "v"(d0), [d1] "v"(d1), [d2] "v"(d2), [d3] "v"(d3), [b] "v"(base), [s0] "v"(s[0]),
+        : [p] "+v"(ptr), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3),
+          [m4] "=&s"(m4), [m5] "=&s"(m5), [m6] "=&s"(m6), [m7] "=&s"(m7)
+        : [d0] "v"(d0), [d1] "v"(d1), [d2] "v"(d2), [d3] "v"(d3), [s0] "v"(s[0]),
           [s1] "v"(s[1]), [s2] "v"(s[2]), [s3] "v"(s[3]), [s4] "v"(s[4]), [s5] "v"(s[5]),
           [s6] "v"(s[6]), [s7] "v"(s[7])
         : "memory");

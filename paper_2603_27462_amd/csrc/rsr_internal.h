@@ -11,41 +11,53 @@
 namespace rsr {
 
 constexpr int kMaxWaves = 16;          // waves per workgroup in the multiply kernel
-constexpr int kLoad = 512;             // stream entries one 16-byte-per-lane wave load covers
+constexpr int kSlab = 512;             // stream entries of one slab: 64 lanes x 8 entries (16 bytes per lane)
+constexpr int kGroupSlabs = 4;         // slabs a wave requests together
 constexpr int kMaxCols = 32766;        // index 'cols' is the zero slot and must fit 15 bits
 constexpr int kSmallCols = 16383;      // up to here an entry is tail<<15 | idx<<1
 constexpr int kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
-constexpr int kLdsMisc = 1024;         // wave-total terms of the scatter phase
 constexpr int kDenseRows = 16;         // dense comparison kernel: rows per workgroup
 constexpr int kDenseTileCols = 256;    // and columns per 16-byte-per-lane tile
 
 // One pass of an RSR handle (binary, M+, M- or fused).
 //
-// Multiply-kernel stream of a block: C chunks of 64*8*H entries.  In stream
-// order a chunk is 64 strips of 8*H consecutive entries, strip l belonging to
-// lane l; in memory it is H slabs of 512 entries, slab h holding entries
-// 8h..8h+7 of every strip, lane after lane, so that each of the H loads of a
-// wave is one contiguous 1 KiB read.  codes[chunk][l] is the group code of the
-// first tail entry at or after the start of strip l.
+// Multiply-kernel stream of a block: in stream order, for every group of identical
+// columns in ascending pattern code (group 0, which contributes nothing, left out), the
+// columns of the group, the last one flagged as tail.  The stream is cut into S slabs of
+// 512 entries; wave w of the block's workgroup owns n_w = S/W + (w < S%W) consecutive
+// slabs, lane l of the wave owns the strip of 8*n_w consecutive entries starting at
+// entry l*8*n_w of the wave's part, and in memory slab h of a wave holds entries
+// 8h..8h+7 of each of its 64 strips, lane after lane, so that every load of a wave is
+// one contiguous KiB.  Each tail stores one prefix sum into a slot of the LDS array E:
+//   indexed by code  slot = pattern code; an empty group has a placeholder entry (tail
+//                    flag, zero slot of v), so every code 1..P-1 owns exactly one tail
+//   indexed by rank  slot = rank of the group among the non-empty ones (1-based);
+//                    no placeholders; the weights of every slot come from gword
+// start[w][l] is the slot of the first tail at or after the start of strip (w, l).
 struct PassData {
     uint16_t *pi = nullptr;       // canonical column permutation  [nb][cols]
     uint32_t *off = nullptr;      // canonical group boundaries    [nb][P+1]
-    uint16_t *entries = nullptr;  // [nb][C][H][64][8]
-    uint16_t *codes = nullptr;    // [nb][C][64]
-    int8_t *wsign = nullptr;      // [nb][W][16]: weight of wave w's total in output row r
-    int64_t C = 0;                // chunks per block
+    uint16_t *entries = nullptr;  // [nb][S][64][8]
+    uint16_t *start = nullptr;    // [nb][W][64]
+    // sign (2 bits, two's complement) of digit r of the code of the first group closed at or
+    // after the start of the strip that follows strip (w, l); 0 when there is none.
+    //   by code: [nb][k][64] words, (r, l) holds the W strips (w, l) at bits 2w (16-bit words
+    //            when W <= 8, else 32-bit)
+    //   by rank: [nb][W][64] 32-bit words, (w, l) holds the k rows at bits 2r
+    void *sgn = nullptr;
+    uint32_t *gword = nullptr;    // by rank: [nb][slots] difference weights of every slot, fw bits per row
+    uint32_t *gcount = nullptr;   // by rank: [nb] non-empty groups of the block
+    int64_t S = 0;                // slabs per block
     float sign = 1.0f;
 };
 
-// Launch-time constants of the scatter phase and the split of chunks over waves.
+// Launch-time constants of the code-indexed scatter phase.
 struct FoldShape {
     int m = 0, Tc = 0, Q = 0;   // Tc = base^m classes handled by stage 1, Q = P / Tc
     int parts = 1;              // threads sharing one class in level 1 (1 or 2)
     int cnt1 = 0;               // entries every level-1 thread adds: ceil(Q / parts)
-    int nact = 0;               // waves that hold fold threads
     int nrows = 0;              // entries per row of the weight table: max(Tc, Q)
     int G = 0;                  // groups of 256 entries per row
-    unsigned short cb[2][kMaxWaves + 1] = {};  // per pass: wave w owns chunks [cb[w], cb[w+1])
 };
 
 }  // namespace rsr
@@ -53,14 +65,15 @@ struct FoldShape {
 struct rsr_handle_s {
     uint32_t magic = 0;
     int kind = 0, k = 0, base = 0, npass = 0, device = 0;
-    int W = 0;    // waves per workgroup of the multiply kernel
-    int H = 0;    // 16-byte loads per lane per chunk (1, 2 or 4)
-    int enc = 0;  // entry encoding: kEncSmall or kEncBig
+    int W = 0;        // waves per workgroup of the multiply kernel
+    int enc = 0;      // entry encoding: kEncSmall or kEncBig
+    int by_rank = 0;  // E indexed by group rank (no placeholders) instead of by pattern code
     int64_t rows = 0, cols = 0, nb = 0, P = 0;
+    int64_t slots = 0;  // entries of E: P (by code) or 1 + the most non-empty groups of a block
     rsr::PassData pass[2];
     rsr::FoldShape fold;
-    uint32_t *fpack = nullptr;   // scatter-phase weights, four per dword: [k][fold.G][64]
-    uint32_t *fshare = nullptr;  // first entry of the level-1 share of every thread [W*64]
+    uint32_t *fpack = nullptr;   // by code: scatter-phase weights, four per dword: [k][fold.G][64]
+    uint32_t *fshare = nullptr;  // by code: first entry of the level-1 share of every thread [W*64]
     bool stale = false;          // a failed rsr_preprocess_into left the buffers half-written
     uint8_t *packed = nullptr;   // dense kind: [rows/16][tiles][64 lanes][16 bytes], row_bytes = 64 tiles
     int64_t row_bytes = 0;
@@ -79,16 +92,20 @@ enum { kEncSmall = 0, kEncBig = 1 };
 enum { MODE_BINARY = 0, MODE_POS = 1, MODE_NEG = 2, MODE_FUSED3 = 3 };
 
 // --- preprocessing launches (null stream) ------------------------------------
+hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t count);
 hipError_t launch_encode(const int8_t *M, int64_t rows, int64_t cols, int k, int mode,
                          uint16_t *code, int *err_flag);
 hipError_t launch_sort(const uint16_t *code, int64_t nb, int64_t cols, int k, int base, int64_t P,
                        uint16_t *pi, uint32_t *off);
-hipError_t launch_stream_len(const uint32_t *off, int64_t nb, int64_t cols, int64_t P,
-                             uint32_t *lens, uint32_t *longest);
-hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t count);
-hipError_t launch_pack_stream(const uint16_t *pi, const uint32_t *off, int64_t nb, int64_t cols,
-                              int64_t P, int64_t C, int H, int enc, uint16_t *scratch,
-                              uint16_t *entries, uint16_t *codes, int *err_flag);
+// stats[0..2] = max over blocks of: columns outside group 0; the same plus the empty groups
+// among codes 1..P-1; the non-empty groups among codes 1..P-1 (the caller zeroes them)
+hipError_t launch_stream_stats(const uint32_t *off, int64_t nb, int64_t cols, int64_t P,
+                               uint32_t *stats);
+// Everything the multiply kernel reads of one pass, from the canonical pi / off:
+// `logical` is scratch of nb * S * kSlab entries, `gcode` scratch of nb * slots entries
+// (by rank only).  *err_flag |= 2 when a block does not hold the expected number of tails.
+hipError_t launch_pack_pass(const rsr_handle_s *h, int pass, uint16_t *logical, uint16_t *gcode,
+                            int *err_flag);
 hipError_t launch_transpose(const int8_t *M, int64_t rows, int64_t cols, int8_t *T);
 hipError_t launch_pack2(const int8_t *M, int64_t rows, int64_t cols, int64_t row_bytes,
                         uint8_t *packed, int *err_flag);
@@ -98,23 +115,23 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
                              float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
 hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale,
                                float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
-const char *rsr_matvec_kernel_name(int v_dtype, int H, int enc, int npass, bool single);
-// True when every pass has at most W chunks per block (one chunk per wave, no loops).
-bool matvec_is_single(const rsr_handle_s *h);
+// Writes the name of the multiply kernel h launches for (v_dtype, batch) into buf.
+void rsr_matvec_kernel_name(const rsr_handle_s *h, int v_dtype, char *buf, size_t len);
 const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype);
 
-// Picks the chunk size (H loads of 512 entries per wave) and the number of
-// waves per workgroup for nb blocks whose longest stream has `longest` entries.
-// The environment variables RSR_H and RSR_W override the choice (tuning only).
-void choose_launch_shape(int64_t longest, int64_t nb, int *H, int *W);
+// Waves per workgroup for nb blocks whose longest stream has `slabs` slabs.
+int choose_waves(int64_t slabs, int64_t nb);
+// True when E is better indexed by group rank: P floats do not fit LDS, or the placeholders
+// of a code-indexed stream would outweigh the per-group weight words.
+bool choose_by_rank(int64_t P, int64_t cols, int64_t longest_by_code, int64_t longest_by_rank,
+                    int64_t most_groups);
 
-
-void make_fold_shape(int base, int k, int64_t P, int W, const int64_t C[2], int npass,
-                     FoldShape *fs);
+void make_fold_shape(int base, int k, int64_t P, int W, FoldShape *fs);
 hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int W, uint32_t *fpack,
                               uint32_t *fshare);
-hipError_t launch_wave_signs(int base, int k, const uint16_t *codes, int64_t nb, int64_t C, int W,
-                             const FoldShape &fs, int pass, int8_t *wsign);
+
+// bits per row in a gword: differences of two signs
+inline int gword_field_bits(int base) { return base == 2 ? 2 : 3; }
 
 // Dynamic LDS beyond 64 KiB has to be enabled per kernel and device.  `enabled` is the
 // kernel's table of the largest size enabled so far on each device (zero-initialised
@@ -130,11 +147,13 @@ inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, int devic
     return e;
 }
 
-// LDS bytes the RSR multiply kernel needs: v and its zero slot, the wave-total terms,
-// E[P] followed by a row of zeros (at most one per thread), and one level-1 sum per thread.
-inline int64_t matvec_lds_bytes(int64_t P, int64_t cols, int v_elem_bytes, int W) {
+// LDS bytes the RSR multiply kernel needs: v and its zero slot, one total per strip, E, and
+// behind E either a row of zeros and one level-1 sum per thread (by code) or one partial
+// per (wave, row) (by rank).
+inline int64_t matvec_lds_bytes(int64_t slots, int64_t cols, int v_elem_bytes, int W, bool by_rank) {
     const int64_t vbytes = ((cols + 1) * v_elem_bytes + 15) / 16 * 16;
-    return vbytes + kLdsMisc + P * 4 + 2 * (int64_t)W * 64 * 4;
+    const int64_t tail = by_rank ? (int64_t)W * 16 * 4 : 2 * (int64_t)W * 64 * 4;
+    return vbytes + (int64_t)W * 64 * 4 + slots * 4 + tail;
 }
 
 }  // namespace rsr

@@ -9,8 +9,6 @@
 //                the compact stream the multiply kernel reads: 16-bit entries,
 //                zero-contribution group dropped, one tail flag per group,
 //                laid out for coalesced per-lane strips
-#include <cstdlib>
-
 #include "rsr_internal.h"
 
 namespace rsr {
@@ -151,13 +149,19 @@ __global__ __launch_bounds__(kThreads) void k_sort(const uint16_t *__restrict__ 
     }
 }
 
-// lens[b] = stream entries of block b: columns outside group 0 plus one
-// placeholder for every empty group among codes 1..P-1; *longest = max over blocks
-// (the caller zeroes it).
-__global__ __launch_bounds__(kThreads) void k_stream_len(const uint32_t *__restrict__ off,
-                                                         int64_t nb, int64_t n, int64_t P,
-                                                         uint32_t *__restrict__ lens,
-                                                         uint32_t *__restrict__ longest) {
+// Slabs wave w owns when S slabs are dealt to W waves, the longer shares first.
+__device__ __forceinline__ void wave_share(int S, int W, int w, int *first, int *count) {
+    const int per = S / W, rem = S - per * W;
+    *first = w * per + min(w, rem);
+    *count = per + (w < rem ? 1 : 0);
+}
+
+// stats[0] = max over blocks of the columns outside group 0; stats[1] = the same plus one
+// placeholder per empty group among codes 1..P-1; stats[2] = most non-empty groups among
+// codes 1..P-1.  The caller zeroes stats.
+__global__ __launch_bounds__(kThreads) void k_stream_stats(const uint32_t *__restrict__ off,
+                                                           int64_t nb, int64_t n, int64_t P,
+                                                           uint32_t *__restrict__ stats) {
     __shared__ uint32_t empties;
     for (int64_t b = blockIdx.x; b < nb; b += gridDim.x) {
         const uint32_t *ob = off + b * (P + 1);
@@ -168,31 +172,38 @@ __global__ __launch_bounds__(kThreads) void k_stream_len(const uint32_t *__restr
         if (mine) atomicAdd(&empties, mine);
         __syncthreads();
         if (threadIdx.x == 0) {
-            const uint32_t len = (uint32_t)(n - ob[1]) + empties;
-            lens[b] = len;
-            atomicMax(longest, len);
+            const uint32_t real = (uint32_t)(n - ob[1]);
+            atomicMax(&stats[0], real);
+            atomicMax(&stats[1], real + empties);
+            atomicMax(&stats[2], (uint32_t)(P - 1) - empties);
         }
         __syncthreads();
     }
 }
 
-// Stream of block b: for code c = 1..P-1 in order, the columns of group c in
-// ascending order (entry = column<<1, last one |1), or one placeholder entry
-// (zero slot = index n, tail bit set) when the group is empty; then filler
-// entries (zero slot, no tail) up to S.  Hence every code 1..P-1 owns exactly
-// one tail entry, and a reader can recover codes by counting tails.
+// Logical stream of block b (L entries): for code c = 1..P-1 in order, the columns of
+// group c in ascending order (entry = column<<1, last one |1).  Indexed by code: an empty
+// group contributes one placeholder entry (zero slot = index n, tail bit set), so that
+// every code owns exactly one tail.  Indexed by rank: empty groups contribute nothing and
+// gcode[b][rank] records the code of every non-empty group (rank 1.., gcode[b][0] = 0,
+// zeros behind the last one), gcount[b] their number.  Filler entries (zero slot, no tail)
+// up to L.
 __global__ __launch_bounds__(kThreads) void k_pack_stream(const uint16_t *__restrict__ pi,
                                                           const uint32_t *__restrict__ off,
-                                                          int64_t nb, int n, int64_t P, int64_t S,
-                                                          uint16_t *__restrict__ stream) {
+                                                          int64_t nb, int n, int64_t P, int64_t L,
+                                                          int by_rank, int64_t slots,
+                                                          uint16_t *__restrict__ stream,
+                                                          uint16_t *__restrict__ gcode,
+                                                          uint32_t *__restrict__ gcount) {
     __shared__ uint32_t wsum[kWaves];
     const uint16_t zero_entry = (uint16_t)(n << 1);
     for (int64_t b = blockIdx.x; b < nb; b += gridDim.x) {
         const uint16_t *pib = pi + b * n;
         const uint32_t *ob = off + b * (P + 1);
-        uint16_t *sb = stream + b * S;
+        uint16_t *sb = stream + b * L;
+        uint16_t *gb = by_rank ? gcode + b * slots : nullptr;
         const uint32_t off1 = ob[1];
-        uint32_t carry = 0;
+        uint32_t carry = 0;  // empty groups among the codes before the current batch
         for (int64_t c0 = 1; c0 < P; c0 += kThreads) {
             const int64_t c = c0 + threadIdx.x;
             const bool valid = c < P;
@@ -201,45 +212,59 @@ __global__ __launch_bounds__(kThreads) void k_pack_stream(const uint16_t *__rest
             uint32_t total;
             const uint32_t eb = carry + wg_exclusive_scan(empty, wsum, &total);
             if (valid) {
-                const uint32_t dst = s - off1 + eb;
                 if (empty) {
-                    sb[dst] = zero_entry | 1;
+                    if (!by_rank) sb[s - off1 + eb] = zero_entry | 1;
                 } else {
+                    const uint32_t dst = s - off1 + (by_rank ? 0u : eb);
                     for (uint32_t t = s; t < e; ++t)
                         sb[dst + (t - s)] = (uint16_t)((pib[t] << 1) | (t + 1 == e ? 1 : 0));
+                    if (by_rank) gb[c - eb] = (uint16_t)c;
                 }
             }
             carry += total;
         }
-        const int64_t len = (int64_t)(n - off1) + carry;
-        for (int64_t t = len + threadIdx.x; t < S; t += kThreads) sb[t] = zero_entry;
+        const int64_t len = (int64_t)(n - off1) + (by_rank ? 0 : carry);
+        for (int64_t t = len + threadIdx.x; t < L; t += kThreads) sb[t] = zero_entry;
+        if (by_rank) {
+            const int64_t count = P - 1 - carry;
+            if (threadIdx.x == 0) { gcount[b] = (uint32_t)count; gb[0] = 0; }
+            for (int64_t r = count + 1 + threadIdx.x; r < slots; r += kThreads) gb[r] = 0;
+        }
+        __syncthreads();
     }
 }
 
 // Reorders the logical stream inside its groups so that the LDS gathers of the multiply
-// kernel collide less.  Gather instruction i of a wave reads entry i of all 64 strips of a
-// chunk; the LDS serves the two half-waves side by side and needs one cycle per distinct
-// dword that falls on the same of its 32 banks.  The order of the columns inside a group
-// is free for the kernel (sums commute up to rounding; the canonical pi is not touched),
-// so for every run of entries of one group inside a strip, each slot takes the remaining
-// column whose bank (for a bf16 vector: (col / 2) mod 32) is least loaded so far in that
-// slot of the half-wave; two more sweeps re-place every strip against all the others.
-// One wave per (block, chunk): thread = (half-wave, slot), strips in order; the first slot
-// of a run places the run.
+// kernel collide less.  Gather instruction i of a wave reads entry i of all 64 strips of
+// the wave; the LDS serves the two half-waves side by side and needs one cycle per
+// distinct dword that falls on the same of its 32 banks.  The order of the columns inside
+// a group is free for the kernel (sums commute up to rounding; the canonical pi is not
+// touched), so for every run of entries of one group inside a strip, each slot takes the
+// remaining column whose banks are least loaded so far in that slot of the half-wave --
+// counted for both vector types the kernel serves: bank (col / 2) mod 32 for 2-byte
+// elements and col mod 32 for 4-byte elements; two more sweeps re-place every strip
+// against all the others.  One wave per (block, wave of the multiply kernel): thread =
+// (half-wave, slot), strips in order; the first slot of a run places the run.  Strips of
+// more than 32 entries are left as they are.
 constexpr int kSpreadSweeps = 3;
 constexpr int kSpreadMaxRun = 8;
 
 __global__ __launch_bounds__(64) void k_spread_banks(uint16_t *__restrict__ logical, int64_t nb,
-                                                     int64_t C, int H) {
-    __shared__ uint8_t load[2][32][33];   // [half][slot][bank], padded
-    __shared__ uint16_t strip[64][33];    // the chunk: [strip][slot], padded
-    const int epl = 8 * H;
+                                                     int S, int W) {
+    __shared__ uint8_t load2[2][32][33];  // [half][slot][bank of a 2-byte element], padded
+    __shared__ uint8_t load4[2][32][33];  // [half][slot][bank of a 4-byte element]
+    __shared__ uint16_t strip[64][33];    // the wave's part: [strip][slot], padded
     const int half = threadIdx.x >> 5, slot = threadIdx.x & 31;
-    const bool live = slot < epl;
-    for (int64_t chunk = blockIdx.x; chunk < nb * C; chunk += gridDim.x) {
-        uint16_t *cb = logical + chunk * 64 * epl;
+    for (int64_t unit = blockIdx.x; unit < nb * W; unit += gridDim.x) {
+        const int64_t b = unit / W;
+        int first, count;
+        wave_share(S, W, (int)(unit - b * W), &first, &count);
+        const int epl = 8 * count;
+        if (epl == 0 || epl > 32) continue;
+        const bool live = slot < epl;
+        uint16_t *cb = logical + (b * S + first) * kSlab;
         for (int i = threadIdx.x; i < 64 * epl; i += 64) strip[i / epl][i % epl] = cb[i];
-        for (int k = 0; k < 33; ++k) load[half][slot][k] = 0;
+        for (int k = 0; k < 33; ++k) { load2[half][slot][k] = 0; load4[half][slot][k] = 0; }
         __syncthreads();
         for (int sweep = 0; sweep < kSpreadSweeps; ++sweep) {
             for (int l = 0; l < 32; ++l) {
@@ -251,7 +276,10 @@ __global__ __launch_bounds__(64) void k_spread_banks(uint16_t *__restrict__ logi
                 const uint32_t tails = (uint32_t)(ball >> (32 * half));
                 if (live) {
                     st[slot] = (uint16_t)(entry >> 1);  // columns only while the strip is placed
-                    if (sweep > 0) --load[half][slot][(entry >> 2) & 31];
+                    if (sweep > 0) {
+                        --load2[half][slot][(entry >> 2) & 31];
+                        --load4[half][slot][(entry >> 1) & 31];
+                    }
                 }
                 __syncthreads();
                 const bool start = live && (slot == 0 || ((tails >> (slot - 1)) & 1u));
@@ -264,15 +292,16 @@ __global__ __launch_bounds__(64) void k_spread_banks(uint16_t *__restrict__ logi
                     const bool place = e - slot < kSpreadMaxRun;
                     for (int sl = slot; sl <= e; ++sl) {
                         int best = sl;
-                        uint8_t bl = load[half][sl][(st[sl] >> 1) & 31];
+                        int bl = load2[half][sl][(st[sl] >> 1) & 31] + load4[half][sl][st[sl] & 31];
                         for (int t = sl + 1; place && t <= e; ++t) {
-                            const uint8_t x = load[half][sl][(st[t] >> 1) & 31];
+                            const int x = load2[half][sl][(st[t] >> 1) & 31] + load4[half][sl][st[t] & 31];
                             if (x < bl) { bl = x; best = t; }
                         }
                         const uint16_t c = st[best];
                         st[best] = st[sl];
                         st[sl] = c;
-                        ++load[half][sl][(c >> 1) & 31];
+                        ++load2[half][sl][(c >> 1) & 31];
+                        ++load4[half][sl][c & 31];
                     }
                 }
                 __syncthreads();
@@ -285,42 +314,136 @@ __global__ __launch_bounds__(64) void k_spread_banks(uint16_t *__restrict__ logi
     }
 }
 
-// Final layout of the stream (see PassData): re-encodes the entries, moves
-// them to the lane-major slabs, and records for every lane strip the group
-// code of the first tail at or after its start (1 + tails before it).  Also
-// checks that the block holds exactly P-1 tails.
+// Final layout of the stream (see PassData): re-encodes the entries, moves them to the
+// slabs, and records for every strip the slot of the first tail at or after its start
+// (1 + tails before it).  Also checks that the block holds the expected number of tails:
+// P - 1 (indexed by code) or gcount[b] (indexed by rank).
 __global__ __launch_bounds__(kThreads) void k_finalize_stream(
-    const uint16_t *__restrict__ logical, int64_t nb, int64_t P, int64_t C, int H, int enc,
-    uint16_t *__restrict__ entries, uint16_t *__restrict__ codes, int *__restrict__ err_flag) {
+    const uint16_t *__restrict__ logical, int64_t nb, int64_t P, int S, int W, int enc,
+    const uint32_t *__restrict__ gcount, uint16_t *__restrict__ entries,
+    uint16_t *__restrict__ start, int *__restrict__ err_flag) {
     __shared__ uint32_t wsum[kWaves];
-    const int epl = 8 * H;
-    const int64_t S = C * 64 * epl;
-    const int64_t strips = C * 64;
+    const int strips = W * 64;
     for (int64_t b = blockIdx.x; b < nb; b += gridDim.x) {
-        const uint16_t *lb = logical + b * S;
+        const uint16_t *lb = logical + b * S * kSlab;
         uint32_t carry = 1;
-        for (int64_t g0 = 0; g0 < strips; g0 += kThreads) {
-            const int64_t g = g0 + threadIdx.x;
+        for (int g0 = 0; g0 < strips; g0 += kThreads) {
+            const int g = g0 + threadIdx.x;
+            const int w = g >> 6, lane = g & 63;
+            int first = 0, count = 0;
+            if (g < strips) wave_share(S, W, w, &first, &count);
+            const int epl = 8 * count;
+            const uint16_t *sp = lb + (int64_t)first * kSlab + (int64_t)lane * epl;
             uint32_t cnt = 0;
-            if (g < strips)
-                for (int i = 0; i < epl; ++i) cnt += lb[g * epl + i] & 1u;
+            for (int i = 0; i < epl; ++i) cnt += sp[i] & 1u;
             uint32_t total;
             const uint32_t ex = wg_exclusive_scan(cnt, wsum, &total);
             if (g < strips) {
-                const int64_t chunk = g >> 6;
-                const int lane = (int)(g & 63);
-                codes[(b * C + chunk) * 64 + lane] = (uint16_t)(carry + ex);
+                start[(b * W + w) * 64 + lane] = (uint16_t)(carry + ex);
                 for (int i = 0; i < epl; ++i) {
-                    const uint32_t e = lb[g * epl + i];
+                    const uint32_t e = sp[i];
                     const uint32_t out = (enc == kEncSmall) ? (((e & 1u) << 15) | (e & 0xfffeu)) : e;
-                    entries[(((b * C + chunk) * H + (i >> 3)) * 64 + lane) * 8 + (i & 7)] =
-                        (uint16_t)out;
+                    entries[(((b * S + first + (i >> 3)) * 64) + lane) * 8 + (i & 7)] = (uint16_t)out;
                 }
             }
             carry += total;
         }
-        if (threadIdx.x == 0 && (int64_t)carry != P) atomicOr(err_flag, 2);
+        const int64_t expect = gcount ? (int64_t)gcount[b] : P - 1;
+        if (threadIdx.x == 0 && (int64_t)carry != expect + 1) atomicOr(err_flag, 2);
+        __syncthreads();
     }
+}
+
+// Sign of digit r of code c as a 2-bit two's complement field (00: 0, 01: +1, 11: -1).
+__device__ __forceinline__ uint32_t sign2_of(uint32_t c, int r, int base) {
+    for (int i = 0; i < r; ++i) c /= (uint32_t)base;
+    const uint32_t d = c % (uint32_t)base;
+    return d == 0 ? 0u : d == 1 ? 1u : 3u;
+}
+__device__ __forceinline__ int sign_of(uint32_t c, int r, int base) {
+    const uint32_t s = sign2_of(c, r, base);
+    return s == 3u ? -1 : (int)s;
+}
+
+// Code of the first group closed at or after the start of the strip that follows strip g of
+// block b; false when there is none (last strip, or no tail from there on).
+__device__ __forceinline__ bool next_strip_code(const uint16_t *__restrict__ start, int64_t b, int g,
+                                                int strips, int64_t P,
+                                                const uint16_t *__restrict__ gcode,
+                                                const uint32_t *__restrict__ gcount, int64_t slots,
+                                                uint32_t *code) {
+    if (g + 1 >= strips) return false;
+    const uint32_t slot = start[b * strips + g + 1];
+    if (gcode) {
+        if (slot > gcount[b]) return false;
+        *code = gcode[b * slots + slot];
+        return true;
+    }
+    if ((int64_t)slot >= P) return false;
+    *code = slot;
+    return true;
+}
+
+// Strip signs, indexed by code: word (b, r, l) holds, at bits 2w, the sign of digit r of the
+// code that follows strip (w, l).  16-bit words when W <= 8.
+__global__ __launch_bounds__(kThreads) void k_strip_signs_rows(const uint16_t *__restrict__ start,
+                                                               int64_t nb, int W, int k, int base,
+                                                               int64_t P, void *__restrict__ sgn) {
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= nb * k * 64) return;
+    const int lane = (int)(gid & 63);
+    const int r = (int)((gid >> 6) % k);
+    const int64_t b = (gid >> 6) / k;
+    uint32_t word = 0;
+    for (int w = 0; w < W; ++w) {
+        uint32_t c;
+        if (next_strip_code(start, b, w * 64 + lane, W * 64, P, nullptr, nullptr, 0, &c))
+            word |= sign2_of(c, r, base) << (2 * w);
+    }
+    if (W <= 8)
+        static_cast<uint16_t *>(sgn)[gid] = (uint16_t)word;
+    else
+        static_cast<uint32_t *>(sgn)[gid] = word;
+}
+
+// Strip signs, indexed by rank: word (b, w, l) holds, at bits 2r, the sign of digit r of
+// the code that follows strip (w, l).
+__global__ __launch_bounds__(kThreads) void k_strip_signs_strips(
+    const uint16_t *__restrict__ start, int64_t nb, int W, int k, int base, int64_t P,
+    const uint16_t *__restrict__ gcode, const uint32_t *__restrict__ gcount, int64_t slots,
+    uint32_t *__restrict__ sgn) {
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= nb * W * 64) return;
+    const int g = (int)(gid % (W * 64));
+    const int64_t b = gid / (W * 64);
+    uint32_t word = 0, c;
+    if (next_strip_code(start, b, g, W * 64, P, gcode, gcount, slots, &c))
+        for (int r = 0; r < k; ++r) word |= sign2_of(c, r, base) << (2 * r);
+    sgn[gid] = word;
+}
+
+// Weights of the slots of a rank-indexed E: field r of gword[b][s] (fw bits, two's
+// complement) = sgn_r(code of rank s) - sgn_r(code of rank s+1), the second term 0 behind
+// the last group; 0 for s = 0 and behind the last group.
+__global__ __launch_bounds__(kThreads) void k_group_words(const uint16_t *__restrict__ gcode,
+                                                          const uint32_t *__restrict__ gcount,
+                                                          int64_t nb, int64_t slots, int k, int base,
+                                                          int fw, uint32_t *__restrict__ gword) {
+    const int64_t gid = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (gid >= nb * slots) return;
+    const int64_t b = gid / slots, s = gid - b * slots;
+    const int64_t count = gcount[b];
+    uint32_t word = 0;
+    if (s >= 1 && s <= count) {
+        const uint32_t c = gcode[gid];
+        const bool has_next = s < count;
+        const uint32_t cn = has_next ? gcode[gid + 1] : 0u;
+        for (int r = 0; r < k; ++r) {
+            const int wgt = sign_of(c, r, base) - (has_next ? sign_of(cn, r, base) : 0);
+            word |= ((uint32_t)wgt & ((1u << fw) - 1u)) << (fw * r);
+        }
+    }
+    gword[gid] = word;
 }
 
 // Plain fill (used instead of a memset node so that callers may capture the sequence).
@@ -392,10 +515,10 @@ hipError_t launch_transpose(const int8_t *M, int64_t rows, int64_t cols, int8_t 
     return hipGetLastError();
 }
 
-hipError_t launch_stream_len(const uint32_t *off, int64_t nb, int64_t cols, int64_t P,
-                             uint32_t *lens, uint32_t *longest) {
-    hipLaunchKernelGGL(k_stream_len, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, off, nb,
-                       cols, P, lens, longest);
+hipError_t launch_stream_stats(const uint32_t *off, int64_t nb, int64_t cols, int64_t P,
+                               uint32_t *stats) {
+    hipLaunchKernelGGL(k_stream_stats, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, off, nb,
+                       cols, P, stats);
     return hipGetLastError();
 }
 
@@ -405,25 +528,35 @@ hipError_t launch_fill_u32(uint32_t *p, uint32_t value, int64_t count) {
     return hipGetLastError();
 }
 
-hipError_t launch_pack_stream(const uint16_t *pi, const uint32_t *off, int64_t nb, int64_t cols,
-                              int64_t P, int64_t C, int H, int enc, uint16_t *scratch,
-                              uint16_t *entries, uint16_t *codes, int *err_flag) {
-    const int64_t S = C * 64 * 8 * H;
-    hipLaunchKernelGGL(k_pack_stream, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, pi, off, nb,
-                       (int)cols, P, S, scratch);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    {
-        static const bool off = std::getenv("RSR_NO_SPREAD") != nullptr;  // tuning only
-        const int64_t units = nb * C;
-        if (!off)
-            hipLaunchKernelGGL(k_spread_banks, dim3((unsigned)(units < 65536 ? units : 65536)), dim3(64),
-                               0, 0, scratch, nb, C, H);
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
+hipError_t launch_pack_pass(const rsr_handle_s *h, int pass, uint16_t *logical, uint16_t *gcode,
+                            int *err_flag) {
+    const PassData &pd = h->pass[pass];
+    const int64_t nb = h->nb, P = h->P;
+    const int S = (int)pd.S, W = h->W;
+    const int by_rank = h->by_rank;
+    auto blocks_for = [](int64_t threads) { return dim3((unsigned)((threads + kThreads - 1) / kThreads)); };
+    hipLaunchKernelGGL(k_pack_stream, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, pd.pi, pd.off,
+                       nb, (int)h->cols, P, (int64_t)S * kSlab, by_rank, h->slots, logical, gcode,
+                       pd.gcount);
+    if (hipError_t e = hipGetLastError()) return e;
+    const int64_t units = nb * W;
+    hipLaunchKernelGGL(k_spread_banks, dim3((unsigned)(units < 65536 ? units : 65536)), dim3(64), 0, 0,
+                       logical, nb, S, W);
+    if (hipError_t e = hipGetLastError()) return e;
+    hipLaunchKernelGGL(k_finalize_stream, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, logical, nb,
+                       P, S, W, h->enc, by_rank ? pd.gcount : nullptr, pd.entries, pd.start, err_flag);
+    if (hipError_t e = hipGetLastError()) return e;
+    if (by_rank) {
+        hipLaunchKernelGGL(k_strip_signs_strips, blocks_for(nb * W * 64), dim3(kThreads), 0, 0, pd.start,
+                           nb, W, h->k, h->base, P, gcode, pd.gcount, h->slots,
+                           static_cast<uint32_t *>(pd.sgn));
+        if (hipError_t e = hipGetLastError()) return e;
+        hipLaunchKernelGGL(k_group_words, blocks_for(nb * h->slots), dim3(kThreads), 0, 0, gcode,
+                           pd.gcount, nb, h->slots, h->k, h->base, gword_field_bits(h->base), pd.gword);
+    } else {
+        hipLaunchKernelGGL(k_strip_signs_rows, blocks_for(nb * h->k * 64), dim3(kThreads), 0, 0, pd.start,
+                           nb, W, h->k, h->base, P, pd.sgn);
     }
-    hipLaunchKernelGGL(k_finalize_stream, dim3(grid_for_blocks(nb)), dim3(kThreads), 0, 0, scratch,
-                       nb, P, C, H, enc, entries, codes, err_flag);
     return hipGetLastError();
 }
 

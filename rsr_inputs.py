@@ -54,6 +54,20 @@ def column_density_binary(rows: int, cols: int, lo: float = 0.05, hi: float = 0.
     return M
 
 
+def dictionary_binary_matrix(rows: int, cols: int, k: int, patterns: int,
+                             seed: int = BASE_SEED) -> np.ndarray:
+    """Binary matrix whose columns, inside every block of k rows, are drawn from a
+    dictionary of `patterns` random k-entry patterns (heavy redundancy: few groups, long)."""
+    g = _rng(seed)
+    M = np.zeros((rows, cols), dtype=np.int8)
+    for r0 in range(0, rows, k):
+        r1 = min(rows, r0 + k)
+        words = (g.random((k, patterns), dtype=np.float32) < 0.5).astype(np.int8)
+        pick = g.integers(0, patterns, size=cols)
+        M[r0:r1] = words[: r1 - r0, pick]
+    return M
+
+
 # ------------------------------------------------------------------ vectors
 def normal_f32(n: int, seed: int = BASE_SEED + 1) -> np.ndarray:
     return _rng(seed).standard_normal(n, dtype=np.float32)

@@ -73,7 +73,7 @@ def test_metric_workload(kind, k):
 @pytest.mark.parametrize("kind,k", [(rsr.RSR_TERNARY_2PASS, 4), (rsr.RSR_TERNARY_2PASS, 6),
                                     (rsr.RSR_TERNARY_2PASS, 8), (rsr.RSR_TERNARY_2PASS, 10),
                                     (rsr.RSR_TERNARY_FUSED, 4), (rsr.RSR_TERNARY_FUSED, 6),
-                                    (rsr.RSR_TERNARY_FUSED, 8)])
+                                    (rsr.RSR_TERNARY_FUSED, 8), (rsr.RSR_TERNARY_FUSED, 10)])
 def test_uniform_ternary_4096_k_sweep(kind, k):
     M = gen.ternary_matrix(4096, 4096, 1.0 / 3.0, gen.BASE_SEED + 20)
     h = rsr.rsr_preprocess(_dev(M), k, kind)

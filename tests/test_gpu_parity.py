@@ -87,7 +87,15 @@ CASES = [
     (rsr.RSR_TERNARY_FUSED, 22, 14336, 8),    # metric column count
     (rsr.RSR_TERNARY_FUSED, 20, 2560, 9),
     (rsr.RSR_TERNARY_FUSED, 7, 31, 2),
-    (rsr.RSR_TERNARY_FUSED, 5, 20001, 7),
+    (rsr.RSR_TERNARY_FUSED, 5, 20001, 7),     # more than eight waves per block
+    # pattern spaces far larger than the column count: E indexed by group rank
+    (rsr.RSR_TERNARY_FUSED, 130, 4096, 10),
+    (rsr.RSR_TERNARY_FUSED, 33, 700, 10),
+    (rsr.RSR_BINARY, 40, 4096, 15),
+    (rsr.RSR_BINARY, 30, 3000, 13),
+    (rsr.RSR_BINARY, 30, 3000, 14),
+    (rsr.RSR_TERNARY_2PASS, 20, 2048, 15),
+    (rsr.RSR_TERNARY_2PASS, 45, 30000, 11),
 ]
 
 
@@ -115,6 +123,30 @@ def test_degenerate_matrices(kind):
         h = rsr.rsr_preprocess(_dev(M), k, kind)
         _check_artifacts(h, oracle.preprocess(M, k, KINDS[kind]))
         _check_matvec(h, M, M.shape[1], 7)
+
+
+def test_all_columns_equal_wide():
+    """One group holding every column, at the widest strips: 30000 equal columns."""
+    M = np.ones((26, 30000), np.int8)
+    M[::3] = 0
+    for kind, k in ((rsr.RSR_BINARY, 13), (rsr.RSR_TERNARY_FUSED, 8)):
+        h = rsr.rsr_preprocess(_dev(M), k, kind)
+        _check_artifacts(h, oracle.preprocess(M, k, KINDS[kind]))
+        _check_matvec(h, M, 30000, 19)
+        rsr.rsr_destroy(h)
+
+
+def test_stream_longer_than_one_round_of_slabs():
+    """A code-indexed stream of more than 64 slabs per block: eight waves, each working
+    through several groups of four slabs, the first group short at its front.  30000 columns
+    drawn from 1000 patterns per block of 12 rows: 30000 entries + about 3100 placeholders."""
+    rows, cols, k = 30, 30000, 12
+    M = gen.dictionary_binary_matrix(rows, cols, k, 1000, 17)
+    h = rsr.rsr_preprocess(_dev(M), k, rsr.RSR_BINARY)
+    assert rsr.rsr_algorithmic_bytes(h, rsr.RSR_F32, 1) > 3 * 65 * 1024   # > 64 slabs per block
+    _check_artifacts(h, oracle.preprocess(M, k, oracle.BINARY))
+    _check_matvec(h, M, cols, 23)
+    rsr.rsr_destroy(h)
 
 
 def test_block_height_exceeds_rows():
@@ -276,9 +308,6 @@ def test_errors():
     assert e.value.code == 2
     with pytest.raises(rsr.RsrError) as e:
         rsr.rsr_preprocess(M, 11, rsr.RSR_TERNARY_FUSED)  # k beyond the fused limit
-    assert e.value.code == 3
-    with pytest.raises(rsr.RsrError) as e:
-        rsr.rsr_preprocess(M, 10, rsr.RSR_TERNARY_FUSED)  # 3^10 bins do not fit LDS
     assert e.value.code == 3
     with pytest.raises(rsr.RsrError) as e:
         rsr.rsr_preprocess(M, -2, rsr.RSR_TERNARY_2PASS)

@@ -280,6 +280,23 @@ def test_expand_unit_vectors_ternary(k):
         assert oracle.expand(u, k, oracle.MODE_FUSED3).tolist() == want
 
 
+@pytest.mark.parametrize("k,mode", [(7, "t"), (8, "t"), (9, "t"), (10, "t"), (12, "b"), (15, "b")])
+def test_expand_unit_vectors_large_k_sampled(k, mode):
+    """The block heights the GPU tests use beyond the exhaustive range: a seeded sample of unit
+    vectors (with the first and the last code) against the library's digit strings."""
+    base = 3 if mode == "t" else 2
+    P = base ** k
+    sign = {"0": 0.0, "1": 1.0, "2": -1.0}
+    codes = set(np.random.default_rng(k).integers(0, P, size=300).tolist()) | {0, 1, P - 1, P // 2}
+    for c in sorted(codes):
+        u = np.zeros(P)
+        u[c] = 1.0
+        digits = np.base_repr(c, base).rjust(k, "0")
+        want = [sign[ch] for ch in reversed(digits)]
+        got = oracle.expand(u, k, oracle.MODE_FUSED3 if mode == "t" else oracle.MODE_BINARY)
+        assert got.tolist() == want
+
+
 # -------------------------------------------------------------- 2-bit packing
 def test_pack2_roundtrip_all_bytes():
     for byte in range(256):
