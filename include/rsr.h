@@ -203,6 +203,25 @@ int rsr_num_passes(rsr_handle_t h);       /* 1 or 2; 0 for the dense kind       
 int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch);
 
 /*
+ * Measurement aids (the benchmark's reference legs; no part of the method).
+ *
+ *   rsr_launch_shape  launch geometry of the multiply kernel of an RSR handle for a vector
+ *                     type: workgroups per vector, threads per workgroup, LDS bytes per
+ *                     workgroup (any of the three pointers may be NULL)
+ *   rsr_probe_empty   launches a kernel that does nothing with the given geometry: what a
+ *                     launch costs in a sequence before it moves a byte
+ *   rsr_probe_read    launches a kernel that reads `bytes` (a multiple of 1024, DEVICE
+ *                     memory at src) once, 1 KiB per wave and request, every wave a
+ *                     contiguous share, all requests of a wave up front -- the access
+ *                     pattern of the multiply kernel's stream -- and discards the data;
+ *                     `sink` is a DEVICE word that is never written in practice (may be NULL)
+ * Asynchronous on `stream`, no allocation.
+ */
+int rsr_launch_shape(rsr_handle_t h, int v_dtype, int *workgroups, int *threads, int *lds_bytes);
+int rsr_probe_empty(int workgroups, int threads, int lds_bytes, void *stream);
+int rsr_probe_read(const void *src, int64_t bytes, int workgroups, int threads, void *sink, void *stream);
+
+/*
  * Name of the multiply kernel this handle launches for a vector type (the
  * symbol a profiler reports), or NULL on a bad argument.  Static storage.
  */

@@ -23,7 +23,7 @@ exported_symbols = [
     "rsr_preprocess_transposed", "rsr_serialized_size", "rsr_serialize", "rsr_deserialize",
     "rsr_num_blocks", "rsr_block_height", "rsr_num_patterns", "rsr_num_passes",
     "rsr_algorithmic_bytes",
-    "rsr_kernel_name", "rsr_preprocess_into",
+    "rsr_kernel_name", "rsr_preprocess_into", "rsr_launch_shape", "rsr_probe_empty", "rsr_probe_read",
 ]
 
 
@@ -75,6 +75,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rsr_preprocess_transposed.argtypes = [vp, i64, i64, ci, ci]
     lib.rsr_preprocess_into.restype = ci
     lib.rsr_preprocess_into.argtypes = [vp, vp]
+    lib.rsr_launch_shape.restype = ci
+    lib.rsr_launch_shape.argtypes = [vp, ci, vp, vp, vp]
+    lib.rsr_probe_empty.restype = ci
+    lib.rsr_probe_empty.argtypes = [ci, ci, ci, vp]
+    lib.rsr_probe_read.restype = ci
+    lib.rsr_probe_read.argtypes = [vp, i64, ci, ci, vp, vp]
     lib.rsr_serialized_size.restype = i64
     lib.rsr_serialized_size.argtypes = [vp]
     lib.rsr_serialize.restype = ci
@@ -279,6 +285,31 @@ def rsr_algorithmic_bytes(h: Handle, v_dtype: int = RSR_F32, batch: int = 1) -> 
     if n < 0:
         raise RsrError(rsr_last_error(), "rsr_algorithmic_bytes")
     return n
+
+
+def rsr_launch_shape(h: Handle, v_dtype: int = RSR_F32):
+    """(workgroups per vector, threads per workgroup, LDS bytes per workgroup) of the multiply kernel."""
+    wg, th, lds = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    rc = load_library().rsr_launch_shape(h.ptr, v_dtype, ctypes.byref(wg), ctypes.byref(th), ctypes.byref(lds))
+    if rc:
+        raise RsrError(rc, "rsr_launch_shape")
+    return wg.value, th.value, lds.value
+
+
+def rsr_probe_empty(workgroups: int, threads: int, lds_bytes: int, stream=None) -> None:
+    rc = load_library().rsr_probe_empty(int(workgroups), int(threads), int(lds_bytes), _stream_ptr(stream))
+    if rc:
+        raise RsrError(rc, "rsr_probe_empty")
+
+
+def rsr_probe_read(src, nbytes: int, workgroups: int, threads: int, stream=None) -> None:
+    """src: a CUDA tensor of at least nbytes bytes, read once and discarded."""
+    if src.numel() * src.element_size() < nbytes:
+        raise ValueError("src is smaller than nbytes")
+    rc = load_library().rsr_probe_read(src.data_ptr(), int(nbytes), int(workgroups), int(threads), None,
+                                       _stream_ptr(stream))
+    if rc:
+        raise RsrError(rc, "rsr_probe_read")
 
 
 def rsr_kernel_name(h: Handle, v_dtype: int = RSR_F32) -> str:

@@ -9,11 +9,14 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "librsr.so")
-SOURCES = ["rsr_api.hip", "rsr_preprocess.hip", "rsr_matvec.hip", "rsr_dense.hip"]
+SOURCES = ["rsr_api.hip", "rsr_preprocess.hip", "rsr_matvec.hip", "rsr_dense.hip", "rsr_probe.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # the first kernel arguments (stream and vector pointers, geometry) arrive in registers
+    # instead of through a scalar load at the start of every wave
+    "-mllvm", "-amdgpu-kernarg-preload-count=14",
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

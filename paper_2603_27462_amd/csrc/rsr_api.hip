@@ -616,6 +616,34 @@ int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void 
     return RSR_OK;
 }
 
+int rsr_probe_empty(int workgroups, int threads, int lds_bytes, void *stream) {
+    if (workgroups < 1 || threads < 64 || threads > 1024 || threads % 64 || lds_bytes < 0 ||
+        lds_bytes > rsr::kLdsBytes)
+        return fail(RSR_EINVAL);
+    const hipError_t e = rsr::launch_probe_empty(workgroups, threads, lds_bytes,
+                                                 reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RSR_OK : fail(hip_code(e));
+}
+
+int rsr_probe_read(const void *src, int64_t bytes, int workgroups, int threads, void *sink, void *stream) {
+    if (!src || bytes < 1024 || workgroups < 1 || threads < 64 || threads > 1024 || threads % 64)
+        return fail(RSR_EINVAL);
+    const hipError_t e = rsr::launch_probe_read(src, bytes, workgroups, threads, sink,
+                                                reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? RSR_OK : fail(hip_code(e));
+}
+
+int rsr_launch_shape(rsr_handle_t h, int v_dtype, int *workgroups, int *threads, int *lds_bytes) {
+    if (!good(h) || !is_rsr_kind(h->kind) || (v_dtype != RSR_F32 && v_dtype != RSR_BF16))
+        return fail(RSR_EINVAL);
+    if (workgroups) *workgroups = (int)h->nb;
+    if (threads) *threads = h->W * 64;
+    if (lds_bytes)
+        *lds_bytes = (int)rsr::matvec_lds_bytes(h->slots, h->cols, v_dtype == RSR_BF16 ? 2 : 4, h->W,
+                                                h->by_rank != 0);
+    return RSR_OK;
+}
+
 int rsr_matvec(rsr_handle_t h, const void *v, void *out, void *stream) {
     if (!good(h)) return fail(RSR_EINVAL);
     return rsr_matvec_ex(h, v, RSR_F32, 1.0f, out, 1, h->cols, h->rows, stream);

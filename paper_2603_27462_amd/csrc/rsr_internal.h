@@ -119,6 +119,11 @@ hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype
 void rsr_matvec_kernel_name(const rsr_handle_s *h, int v_dtype, char *buf, size_t len);
 const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype);
 
+// --- reference launches of the benchmark ---------------------------------------------
+hipError_t launch_probe_empty(int workgroups, int threads, int lds_bytes, hipStream_t stream);
+hipError_t launch_probe_read(const void *src, int64_t bytes, int workgroups, int threads, void *sink,
+                             hipStream_t stream);
+
 // Waves per workgroup for nb blocks whose longest stream has `slabs` slabs.
 int choose_waves(int64_t slabs, int64_t nb);
 // True when E is better indexed by group rank: P floats do not fit LDS, or the placeholders
@@ -147,13 +152,14 @@ inline hipError_t ensure_dynamic_lds(const void *kernel, size_t bytes, int devic
     return e;
 }
 
-// LDS bytes the RSR multiply kernel needs: v and its zero slot, one total per strip, E, and
+// LDS bytes the RSR multiply kernel needs: v and its zero slot, one total per strip (at
+// least eight waves' worth), E, and
 // behind E either a row of zeros and one level-1 sum per thread (by code) or one partial
 // per (wave, row) (by rank).
 inline int64_t matvec_lds_bytes(int64_t slots, int64_t cols, int v_elem_bytes, int W, bool by_rank) {
     const int64_t vbytes = ((cols + 1) * v_elem_bytes + 15) / 16 * 16;
     const int64_t tail = by_rank ? (int64_t)W * 16 * 4 : 2 * (int64_t)W * 64 * 4;
-    return vbytes + (int64_t)W * 64 * 4 + slots * 4 + tail;
+    return vbytes + (int64_t)(W < 8 ? 8 : W) * 64 * 4 + slots * 4 + tail;
 }
 
 }  // namespace rsr

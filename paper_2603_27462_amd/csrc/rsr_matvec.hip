@@ -70,6 +70,11 @@ struct OutArgs {
     float scale;
 };
 
+// Slabs of the first group a wave requests before v is staged; the others follow the first
+// barrier.  With all four up front the requests for v queue behind 32 KiB of stream per
+// block and the first barrier comes later (measured: 7.4 -> 7.05 us cold, 6.0 -> 5.85 warm).
+constexpr int kEarlySlabs = 2;
+
 template <typename T>
 __device__ __forceinline__ void pin(T &x) {
     asm volatile("" : "+v"(x));
@@ -96,36 +101,40 @@ __device__ __forceinline__ void pin(T &x) {
 // does not depend on E -- LDS addresses, unpacked weights, predicates -- is therefore
 // computed by prepare_scatter() while the global loads of the pass are still in flight,
 // and pinned in registers until it is used.
-constexpr int kL1Regs = 16;  // level-1 entries per thread covered by prepared addresses
+constexpr int kL1Regs = 16;  // level-1 entries per thread read in one batch
 
 struct ScatterPrep {
-    uint32_t a1[kL1Regs];  // level 1: LDS addresses of the thread's first entries
-    uint32_t c1_store;     // level 1: where the thread's sum goes
-    uint32_t la[8];        // level 2 (one row per wave): class sums / entries of the row
-    uint32_t ta[8];        // level 2: totals of the strips (w, lane), w < 8 (clamped to W - 1)
-    float wf[4];           // level 2: weights of the four elements
+    uint32_t first;     // level 1: LDS address of the thread's first entry (E[0] without a share)
+    uint32_t c1_store;  // level 1: where the thread's sum goes
+    uint32_t la[8];     // level 2 (one row per wave): class sums / entries of the row
+    uint32_t t_lane;    // level 2: total of strip (0, lane); strip (w, lane) is w * 256 bytes on
+    float wf[4];        // level 2: weights of the four elements
     bool has_share;
 };
 
+// TC: the class count as a compile-time constant (0: only known at run time), which turns
+// the strides of level 1 into instruction offsets.
+template <int TC>
+__device__ __forceinline__ uint32_t class_step(const FoldArgs &f) {
+    return TC > 0 ? (uint32_t)TC * 4u : (uint32_t)f.Tc * 4u;
+}
+
+template <int TC>
 __device__ __forceinline__ void prepare_scatter(ScatterPrep &sp, const FoldArgs &f, uint32_t share,
                                                 uint32_t wpre, uint32_t t_at, uint32_t e_at,
                                                 uint32_t c1_at, int W, int w, int lane, int tid) {
-    const uint32_t step = (uint32_t)f.Tc * 4u;
+    const uint32_t step = class_step<TC>(f);
+    const int Tc = TC > 0 ? TC : f.Tc;
     sp.has_share = share != 0xffffffffu;
-    const uint32_t first = e_at + (sp.has_share ? share : 0u) * 4u;
-#pragma unroll
-    for (int i = 0; i < kL1Regs; ++i) {
-        // entries past the share read E[0], which is zero
-        sp.a1[i] = (i < f.cnt1) ? first + (uint32_t)i * step : e_at;
-        pin(sp.a1[i]);
-    }
+    sp.first = e_at + (sp.has_share ? share : 0u) * 4u;
+    pin(sp.first);
     sp.c1_store = c1_at + (uint32_t)tid * 4u;  // C1[part][class]: tid = part * Tc + class
     pin(sp.c1_store);
     // level 2, one row per wave (used when G == 1 and k <= W)
     const int r = min(w, f.k - 1);
     const bool low = r < f.m;
-    const int n = low ? f.Tc : f.Q;
-    const uint32_t base = low ? c1_at : e_at + (uint32_t)(f.Tc - 1) * 4u;
+    const int n = low ? Tc : f.Q;
+    const uint32_t base = low ? c1_at : e_at + (uint32_t)(Tc - 1) * 4u;
     const uint32_t stride = low ? 4u : step;
     const uint32_t last = base + stride * (uint32_t)(n - 1);
     sp.la[0] = min(base + stride * (uint32_t)lane, last);
@@ -138,12 +147,8 @@ __device__ __forceinline__ void prepare_scatter(ScatterPrep &sp, const FoldArgs 
         pin(sp.la[j]);
         pin(sp.la[4 + j]);
     }
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        // strips of waves that do not exist carry sign 0; their address repeats the last wave's
-        sp.ta[j] = t_at + (uint32_t)(min(j, W - 1) * 64 + lane) * 4u;
-        pin(sp.ta[j]);
-    }
+    sp.t_lane = t_at + (uint32_t)lane * 4u;
+    pin(sp.t_lane);
     sp.wf[0] = (float)(int)(signed char)(wpre & 0xffu);
     sp.wf[1] = (float)(int)(signed char)((wpre >> 8) & 0xffu);
     sp.wf[2] = (float)(int)(signed char)((wpre >> 16) & 0xffu);
@@ -152,18 +157,18 @@ __device__ __forceinline__ void prepare_scatter(ScatterPrep &sp, const FoldArgs 
     for (int j = 0; j < 4; ++j) pin(sp.wf[j]);
 }
 
-// Sum over the strips (w, lane) of total * sign; sw holds the signs at bits 2w.
-__device__ __forceinline__ float strip_terms(const ScatterPrep &sp, uint32_t sw, uint32_t t_at,
-                                             int W, int lane) {
+// Sum over the strips (w, lane) of total * sign; sw holds the signs at bits 2w.  The totals
+// of at least eight waves exist in LDS (rows of waves that do not exist are zero).
+__device__ __forceinline__ float strip_terms(const ScatterPrep &sp, uint32_t sw, int W) {
     float t[8];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) t[j] = *lds_float(sp.ta[j]);
+    for (int j = 0; j < 8; ++j) t[j] = *lds_float(sp.t_lane + (uint32_t)j * 256u);
     float x = 0.0f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) x += t[j] * field_as_float(sw, 2 * j, 2);
     if (W > 8) {
         for (int j = 8; j < W; ++j)
-            x += *lds_float(t_at + (uint32_t)(j * 64 + lane) * 4u) * field_as_float(sw, 2 * j, 2);
+            x += *lds_float(sp.t_lane + (uint32_t)j * 256u) * field_as_float(sw, 2 * j, 2);
     }
     return x;
 }
@@ -173,7 +178,7 @@ __device__ __forceinline__ uint32_t load_sign_word(const void *sgn, long long in
                   : static_cast<const uint32_t *>(sgn)[index];
 }
 
-template <bool FIRST>
+template <bool FIRST, int TC>
 __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const ScatterPrep &sp,
                                                 uint32_t wpre, uint32_t sw, const void *sgn,
                                                 long long b, uint32_t t_at, uint32_t e_at,
@@ -181,30 +186,37 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
                                                 float sign_scale, float *out_rows,
                                                 long long rows_left) {
     if (sp.has_share) {
-        float col;
-        if (f.cnt1 <= 4) {
-            const float x0 = *lds_float(sp.a1[0]), x1 = *lds_float(sp.a1[1]);
-            const float x2 = *lds_float(sp.a1[2]), x3 = *lds_float(sp.a1[3]);
-            col = (x0 + x1) + (x2 + x3);
-        } else {
-            float x[kL1Regs];
+        // the thread's cnt1 entries, E[first + i Tc]: whole batches of four, then the rest one
+        // by one (wave-uniform branches; the loads of a batch are in flight together)
+        const uint32_t step = class_step<TC>(f);
+        float x[kL1Regs];
 #pragma unroll
-            for (int i = 0; i < kL1Regs; ++i) x[i] = *lds_float(sp.a1[i]);
-            float rest = 0.0f;
-            if (f.cnt1 > kL1Regs) {
-                const uint32_t step = (uint32_t)f.Tc * 4u;
-                uint32_t at = sp.a1[kL1Regs - 1] + step;
-                for (int i = kL1Regs; i < f.cnt1; ++i) {
-                    rest += *lds_float(at);
-                    at += step;
-                }
+        for (int i = 0; i < kL1Regs; ++i) x[i] = 0.0f;
+        const int n1 = f.cnt1 < kL1Regs ? f.cnt1 : kL1Regs;
+#pragma unroll
+        for (int i0 = 0; i0 < kL1Regs; i0 += 4) {
+            if (i0 + 4 <= n1) {
+#pragma unroll
+                for (int i = i0; i < i0 + 4; ++i) x[i] = *lds_float(sp.first + (uint32_t)i * step);
+            } else {
+#pragma unroll
+                for (int i = i0; i < i0 + 3; ++i)
+                    if (i < n1) x[i] = *lds_float(sp.first + (uint32_t)i * step);
             }
-#pragma unroll
-            for (int d = 1; d < kL1Regs; d *= 2)
-#pragma unroll
-                for (int i = 0; i + d < kL1Regs; i += 2 * d) x[i] += x[i + d];
-            col = x[0] + rest;
         }
+        float rest = 0.0f;
+        if (f.cnt1 > kL1Regs) {
+            uint32_t at = sp.first + (uint32_t)kL1Regs * step;
+            for (int i = kL1Regs; i < f.cnt1; ++i) {
+                rest += *lds_float(at);
+                at += step;
+            }
+        }
+#pragma unroll
+        for (int d = 1; d < kL1Regs; d *= 2)
+#pragma unroll
+            for (int i = 0; i + d < kL1Regs; i += 2 * d) x[i] += x[i + d];
+        const float col = x[0] + rest;
         *lds_float(sp.c1_store) = col;
     }
     __syncthreads();
@@ -214,7 +226,7 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
             const int r = w;
             float v0 = *lds_float(sp.la[0]), v1 = *lds_float(sp.la[1]);
             float v2 = *lds_float(sp.la[2]), v3 = *lds_float(sp.la[3]);
-            float x = strip_terms(sp, sw, t_at, W, lane);
+            float x = strip_terms(sp, sw, W);
             if (r < f.m && f.parts == 2) {
                 const float u0 = *lds_float(sp.la[4]), u1 = *lds_float(sp.la[5]);
                 const float u2 = *lds_float(sp.la[6]), u3 = *lds_float(sp.la[7]);
@@ -238,11 +250,11 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
         const int n = low ? f.Tc : f.Q;
         // element j of the row: class sum C1[0][j] (+ C1[1][j]), or E[Tc j + Tc - 1]
         const uint32_t base = low ? c1_at : e_at + (uint32_t)(f.Tc - 1) * 4u;
-        const uint32_t stride = low ? 4u : (uint32_t)f.Tc * 4u;
+        const uint32_t stride = low ? 4u : class_step<TC>(f);
         const bool two = low && f.parts == 2;
-        const uint32_t second = (uint32_t)f.Tc * 4u;
+        const uint32_t second = class_step<TC>(f);
         const uint32_t swr = (r == w) ? sw : load_sign_word(sgn, (b * f.k + r) * 64 + lane, W);
-        float x = strip_terms(sp, swr, t_at, W, lane);
+        float x = strip_terms(sp, swr, W);
         for (int g = 0; g * 256 < n; ++g) {
             const uint32_t pk = (r == w && g == 0) ? wpre : f.fpack[(r * f.G + g) * 64 + lane];
             const int j0 = lane + 256 * g;
@@ -319,18 +331,23 @@ __device__ __forceinline__ void scatter_by_rank(const FoldArgs &f, const uint32_
 }
 
 // ---- gather + aggregate: one slab of a wave -----------------------------------------------
-// Eight entries per lane: gather the eight elements of v, extend the strip's running sum,
-// and let every tail store its prefix.
+// Eight entries per lane: gather the eight elements of v (slab_gather), then extend the
+// strip's running sum and let every tail store its prefix (slab_finish).  NEWER: LDS
+// operations issued after the gathers that may still be outstanding when they are used.
 template <typename VT, int ENC>
-__device__ __forceinline__ void slab_step(const u32x4 &q, uint32_t (&g)[8], float &prev,
-                                          uint32_t &ptr) {
+__device__ __forceinline__ void slab_gather(const u32x4 &q, uint32_t (&g)[8]) {
     const uint32_t d[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         gather<VT>(g[2 * j], entry_addr<VT, ENC, 0>(d[j]));
         gather<VT>(g[2 * j + 1], entry_addr<VT, ENC, 1>(d[j]));
     }
-    lds_wait<0>(g);
+}
+
+template <int ENC, int NEWER>
+__device__ __forceinline__ void slab_finish(const u32x4 &q, uint32_t (&g)[8], float &prev,
+                                            uint32_t &ptr) {
+    lds_wait<NEWER>(g);
     float s[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -338,51 +355,44 @@ __device__ __forceinline__ void slab_step(const u32x4 &q, uint32_t (&g)[8], floa
         s[i] = prev;
     }
     if (ENC == kEncSmall) {
-        tail_store8_small(d[0], d[1], d[2], d[3], s, ptr);
+        tail_store8_small(q.x, q.y, q.z, q.w, s, ptr);
     } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) tail_store2_big(d[j], s[2 * j], s[2 * j + 1], ptr);
+        tail_store2_big(q.x, s[0], s[1], ptr);
+        tail_store2_big(q.y, s[2], s[3], ptr);
+        tail_store2_big(q.z, s[4], s[5], ptr);
+        tail_store2_big(q.w, s[6], s[7], ptr);
     }
 }
 
 // One pass (binary, M+, M- or fused) of one block.  FIRST: v still has to be staged into
 // LDS and the output rows are overwritten; otherwise the pass adds to them.
-template <typename VT, int ENC, bool BYRANK, bool FIRST>
-__device__ __forceinline__ void run_pass(const PassArgs &a, const void *__restrict__ v, long long ldv,
+template <typename VT, int ENC, bool BYRANK, bool FIRST, int TC>
+__device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
+                                         const uint16_t *__restrict__ start, int S, int per, int rem,
+                                         const PassArgs &a, const void *__restrict__ v, long long ldv,
                                          int n_in, int W, const FoldArgs &f, const OutArgs &o,
                                          int vec) {
-    // LDS (byte addresses): v (n_in + zero slot) | T[W][64] | E[slots] | by code: Tc zeros,
-    // C1[threads]; by rank: partial sums [W][16]
+    // LDS (byte addresses): v (n_in + zero slot) | T[max(W, 8)][64] | E[slots] | by code: Tc
+    // zeros, C1[threads]; by rank: partial sums [W][16]
     const uint32_t vbytes = ((n_in + 1) * (uint32_t)sizeof(VT) + 15u) & ~15u;
     const uint32_t t_at = vbytes;
-    const uint32_t e_at = t_at + (uint32_t)W * 256u;
+    const uint32_t e_at = t_at + (uint32_t)max(W, 8) * 256u;
     const uint32_t z_at = e_at + (uint32_t)f.slots * 4u;
-    const uint32_t c1_at = z_at + (uint32_t)f.Tc * 4u;
+    const uint32_t c1_at = z_at + class_step<TC>(f);
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nthreads = W * 64;
     const long long b = blockIdx.x;
 
     // the wave's slabs, in groups of four; the first group may be short at its front
-    const int S = a.S;
-    const int n_w = a.per + (w < a.rem ? 1 : 0);
-    const int first = w * a.per + min(w, a.rem);
+    const int n_w = per + (w < rem ? 1 : 0);
+    const int first = w * per + min(w, rem);
     const int ngroups = (n_w + kGroupSlabs - 1) / kGroupSlabs;
     const int lead = ngroups * kGroupSlabs - n_w;  // absent slots of the first group
 
-    // ---- every global load of the pass is requested here: the small tables first (they
-    // are turned into scatter-phase constants while the rest is in flight), then v, then
-    // the first group of slabs ------------------------------------------------------------
-    uint32_t share = 0, wpre = 0, sw = 0, count = 0;
-    if (BYRANK) {
-        sw = static_cast<const uint32_t *>(a.sgn)[(b * W + w) * 64 + lane];
-        count = a.gcount[b];
-    } else {
-        share = f.fshare[tid];
-        wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
-        sw = load_sign_word(a.sgn, (b * f.k + min(w, f.k - 1)) * 64 + lane, W);
-    }
-    const uint32_t slot0 = __builtin_nontemporal_load(&a.start[(b * W + w) * 64 + lane]);
+    // ---- the global loads of the pass, in the order of use: v (the first barrier waits for
+    // it), the strip's first slot and the first slabs; behind the first barrier the small
+    // tables of the scatter phase and the remaining slabs ---------------------------------
     const long long vstride = ldv * (long long)sizeof(VT);
     const unsigned char *vg = reinterpret_cast<const unsigned char *>(v) + (long long)vec * vstride;
     const int nbytes = n_in * (int)sizeof(VT);
@@ -399,27 +409,28 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *__restri
         s2 = v16[min(j_2, n16 - 1)];
         s3 = v16[min(j_3, n16 - 1)];
     }
+    const uint32_t slot0 = __builtin_nontemporal_load(&start[(b * W + w) * 64 + lane]);
     // The stream is read once: non-temporal loads keep it out of the way of v and the
     // tables.  Slots without a slab (the front of the first group, waves without slabs)
     // repeat a neighbouring slab and are ignored: no branch, so nothing delays the requests
     // and the number of loads in flight is the same in every wave.
-    const u32x4 *ep = reinterpret_cast<const u32x4 *>(a.entries) + (b * S) * 64 + lane;
+    const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + (b * S) * 64 + lane;
     u32x4 q[kGroupSlabs];
 #pragma unroll
-    for (int j = 0; j < kGroupSlabs; ++j)
+    for (int j = 0; j < kEarlySlabs; ++j)
         q[j] = __builtin_nontemporal_load(&ep[(long long)min(first + max(j - lead, 0), S - 1) * 64]);
-
-    // ---- work that needs no stream data, done while the loads are in flight ----------------
-    ScatterPrep sp;
-    if (!BYRANK) prepare_scatter(sp, f, share, wpre, t_at, e_at, c1_at, W, w, lane, tid);
-    uint32_t g[8];  // gather targets: for bf16 the low halves must be zero
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        g[i] = 0u;
-        pin(g[i]);
-    }
-    if (!BYRANK && tid < f.Tc) *lds_float(z_at + (uint32_t)tid * 4u) = 0.0f;
-    if (tid == 0) *lds_float(e_at) = 0.0f;
+    uint32_t share = 0, wpre = 0, sw = 0, count = 0;
+    auto load_tables = [&]() {
+        if (BYRANK) {
+            sw = static_cast<const uint32_t *>(a.sgn)[(b * W + w) * 64 + lane];
+            count = a.gcount[b];
+        } else {
+            share = f.fshare[tid];
+            wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
+            sw = load_sign_word(a.sgn, (b * f.k + min(w, f.k - 1)) * 64 + lane, W);
+        }
+    };
+    if (kEarlySlabs == kGroupSlabs) load_tables();
 
     // ---- stage v -----------------------------------------------------------------------------
     if (FIRST) {
@@ -440,23 +451,57 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *__restri
         }
         if (tid == 0) lds_store_v<VT>(nbytes, VT(0));
     }
+    // ---- work that needs no stream data, done while the loads are in flight ----------------
+    ScatterPrep sp;
+    if (kEarlySlabs == kGroupSlabs && !BYRANK)
+        prepare_scatter<TC>(sp, f, share, wpre, t_at, e_at, c1_at, W, w, lane, tid);
+    uint32_t g[2][8];  // gather targets: for bf16 the low halves must be zero
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        g[i >> 3][i & 7] = 0u;
+        pin(g[i >> 3][i & 7]);
+    }
+    if (!BYRANK) {
+        if (tid < (TC > 0 ? TC : f.Tc)) *lds_float(z_at + (uint32_t)tid * 4u) = 0.0f;
+        // totals of waves that do not exist (the scatter phase reads eight rows)
+        for (int i = nthreads + tid; i < 8 * 64; i += nthreads) *lds_float(t_at + (uint32_t)i * 4u) = 0.0f;
+    }
+    if (tid == 0) *lds_float(e_at) = 0.0f;
     __syncthreads();
+    if (kEarlySlabs < kGroupSlabs) {
+        load_tables();
+#pragma unroll
+        for (int j = kEarlySlabs; j < kGroupSlabs; ++j)
+            q[j] = __builtin_nontemporal_load(&ep[(long long)min(first + max(j - lead, 0), S - 1) * 64]);
+    }
 
-    // ---- gather + aggregate, slab by slab as the loads return ------------------------------
+    // ---- gather + aggregate, slab by slab as the loads return: the gathers of a slab are
+    // issued before the previous slab's sums and tail stores, so that the LDS always has
+    // reads queued while the wave computes ---------------------------------------------------
     float prev = 0.0f;
     uint32_t ptr = e_at + slot0 * 4u;
     if (ngroups > 0) {
+        // (lead < kGroupSlabs: the last slot always holds a slab)
 #pragma unroll
-        for (int j = 0; j < kGroupSlabs; ++j)
-            if (j >= lead) slab_step<VT, ENC>(q[j], g, prev, ptr);
+        for (int j = 0; j < kGroupSlabs; ++j) {
+            if (j >= lead) slab_gather<VT, ENC>(q[j], g[j & 1]);
+            if (j >= 1 && j - 1 >= lead) slab_finish<ENC, 8>(q[j - 1], g[(j - 1) & 1], prev, ptr);
+        }
+        slab_finish<ENC, 0>(q[kGroupSlabs - 1], g[(kGroupSlabs - 1) & 1], prev, ptr);
         for (int grp = 1; grp < ngroups; ++grp) {
             const u32x4 *gp = ep + (long long)(first + grp * kGroupSlabs - lead) * 64;
 #pragma unroll
             for (int j = 0; j < kGroupSlabs; ++j) q[j] = __builtin_nontemporal_load(&gp[j * 64]);
 #pragma unroll
-            for (int j = 0; j < kGroupSlabs; ++j) slab_step<VT, ENC>(q[j], g, prev, ptr);
+            for (int j = 0; j < kGroupSlabs; ++j) {
+                slab_gather<VT, ENC>(q[j], g[j & 1]);
+                if (j >= 1) slab_finish<ENC, 8>(q[j - 1], g[(j - 1) & 1], prev, ptr);
+            }
+            slab_finish<ENC, 0>(q[kGroupSlabs - 1], g[(kGroupSlabs - 1) & 1], prev, ptr);
         }
     }
+    if (kEarlySlabs < kGroupSlabs && !BYRANK)
+        prepare_scatter<TC>(sp, f, share, wpre, t_at, e_at, c1_at, W, w, lane, tid);
     if (!BYRANK) *lds_float(t_at + (uint32_t)tid * 4u) = prev;
     lds_drain();
     __syncthreads();
@@ -468,19 +513,25 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, const void *__restri
         scatter_by_rank<FIRST>(f, a.gword + b * f.slots, count, sw, prev, e_at, z_at, W, w, lane, tid,
                                o.scale * a.sign, out_rows, rows_left);
     else
-        scatter_by_code<FIRST>(f, sp, wpre, sw, a.sgn, b, t_at, e_at, c1_at, W, w, lane,
-                               o.scale * a.sign, out_rows, rows_left);
+        scatter_by_code<FIRST, TC>(f, sp, wpre, sw, a.sgn, b, t_at, e_at, c1_at, W, w, lane,
+                                   o.scale * a.sign, out_rows, rows_left);
 }
 
-template <typename VT, int ENC, int NPASS, bool BYRANK>
-__global__ __launch_bounds__(1024, 4) void k_rsr_matvec(const PassArgs a0, const void *__restrict__ v,
-                                                        long long ldv, int n_in, int W,
-                                                        const FoldArgs f, const PassArgs a1,
-                                                        const OutArgs o) {
-    run_pass<VT, ENC, BYRANK, true>(a0, v, ldv, n_in, W, f, o, (int)blockIdx.y);
+// TC: 0, or the class count of the code-indexed scatter phase when it is the common one
+// (243 = 3^5: fused ternary blocks of five or more rows with 4 to 11 waves).
+// The arguments every early address depends on come first and as plain values (they can be
+// handed to the wave in registers); the rest is grouped.
+template <typename VT, int ENC, int NPASS, bool BYRANK, int TC>
+__global__ __launch_bounds__(1024, 4) void k_rsr_matvec(
+    const uint16_t *__restrict__ entries0, const uint16_t *__restrict__ start0,
+    const void *__restrict__ v, int S0, int per0, int rem0, int n_in, int W, long long ldv,
+    const PassArgs a0, const FoldArgs f, const PassArgs a1, const OutArgs o) {
+    run_pass<VT, ENC, BYRANK, true, TC>(entries0, start0, S0, per0, rem0, a0, v, ldv, n_in, W, f, o,
+                                        (int)blockIdx.y);
     if (NPASS == 2) {
         __syncthreads();  // the second pass reuses E and the totals
-        run_pass<VT, ENC, BYRANK, false>(a1, v, ldv, n_in, W, f, o, (int)blockIdx.y);
+        run_pass<VT, ENC, BYRANK, false, TC>(a1.entries, a1.start, a1.S, a1.per, a1.rem, a1, v, ldv, n_in,
+                                             W, f, o, (int)blockIdx.y);
     }
 }
 
@@ -495,21 +546,25 @@ struct LaunchArgs {
     hipStream_t stream;
 };
 
-template <typename VT, int ENC, int NPASS, bool BYRANK>
+constexpr int kCommonClasses = 243;
+
+template <typename VT, int ENC, int NPASS, bool BYRANK, int TC>
 hipError_t launch(const LaunchArgs &x) {
     static std::atomic<size_t> enabled[kMaxDevices];
-    auto kern = k_rsr_matvec<VT, ENC, NPASS, BYRANK>;
+    auto kern = k_rsr_matvec<VT, ENC, NPASS, BYRANK, TC>;
     if (hipError_t e = ensure_dynamic_lds(reinterpret_cast<const void *>(kern), x.lds, x.device, enabled))
         return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)x.nblocks, (unsigned)x.batch), dim3(x.W * 64), x.lds,
-                       x.stream, x.a0, x.v, x.ldv, x.n_in, x.W, x.f, x.a1, x.o);
+                       x.stream, x.a0.entries, x.a0.start, x.v, x.a0.S, x.a0.per, x.a0.rem, x.n_in, x.W, x.ldv,
+                       x.a0, x.f, x.a1, x.o);
     return hipGetLastError();
 }
 
 template <typename VT, int ENC>
 hipError_t launch_nr(const LaunchArgs &x, int npass, bool by_rank) {
-    if (by_rank) return npass == 1 ? launch<VT, ENC, 1, true>(x) : launch<VT, ENC, 2, true>(x);
-    return npass == 1 ? launch<VT, ENC, 1, false>(x) : launch<VT, ENC, 2, false>(x);
+    if (by_rank) return npass == 1 ? launch<VT, ENC, 1, true, 0>(x) : launch<VT, ENC, 2, true, 0>(x);
+    if (npass == 1 && x.f.Tc == kCommonClasses) return launch<VT, ENC, 1, false, kCommonClasses>(x);
+    return npass == 1 ? launch<VT, ENC, 1, false, 0>(x) : launch<VT, ENC, 2, false, 0>(x);
 }
 
 // ---- preprocessing-time tables of the code-indexed scatter phase --------------------------
@@ -680,9 +735,10 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
 
 void rsr_matvec_kernel_name(const rsr_handle_s *h, int v_dtype, char *buf, size_t len) {
     // as a profiler prints the instantiation
-    std::snprintf(buf, len, "k_rsr_matvec<%s, %d, %d, %s>",
+    const bool common = !h->by_rank && h->npass == 1 && h->fold.Tc == kCommonClasses;
+    std::snprintf(buf, len, "k_rsr_matvec<%s, %d, %d, %s, %d>",
                   v_dtype == RSR_BF16 ? "unsigned short" : "float", h->enc, h->npass,
-                  h->by_rank ? "true" : "false");
+                  h->by_rank ? "true" : "false", common ? kCommonClasses : 0);
 }
 
 }  // namespace rsr
