@@ -179,38 +179,55 @@ def run_configs(args):
     results = []
 
     def one(name, make_layers, k, kind, bf16, batch=1, max_sets=40):
-        """make_layers(set_index) -> list of int8 matrices (numpy)."""
+        """make_layers(set_index) -> list of int8 matrices (numpy); an entry that is itself a
+        list is a group of sibling layers (same input) served by one stacked handle."""
         vt = rsr.RSR_BF16 if bf16 else rsr.RSR_F32
+
+        def prep(M):
+            if isinstance(M, list):
+                return rsr.rsr_preprocess_stacked([torch.from_numpy(x).to(dev) for x in M], k, kind)
+            return rsr.rsr_preprocess(torch.from_numpy(M).to(dev), k, kind)
+
         try:
-            sets = [[rsr.rsr_preprocess(torch.from_numpy(M).to(dev), k, kind) for M in make_layers(0)]]
+            sets = [[prep(M) for M in make_layers(0)]]
         except rsr.RsrError as e:
             results.append({"workload": name, "kind": kind_name[kind], "k": k, "error": str(e)})
             return
         nbytes = sum(rsr.rsr_algorithmic_bytes(h, vt, batch) for h in sets[0])
         nsets = int(min(max_sets, max(2, np.ceil(COLD_WORKING_SET / nbytes))))
         for i in range(1, nsets):
-            sets.append([rsr.rsr_preprocess(torch.from_numpy(M).to(dev), k, kind) for M in make_layers(i)])
+            sets.append([prep(M) for M in make_layers(i)])
         vs, outs = [], []
         for h in sets[0]:
             shape = (batch, h.cols)
             x = torch.randn(shape, device=dev)
             vs.append(x.to(torch.bfloat16) if bf16 else x)
-            outs.append(torch.empty((nsets, batch, h.rows), dtype=torch.float32, device=dev))
+            if hasattr(h, "layer_rows"):
+                outs.append([[torch.empty(r, dtype=torch.float32, device=dev) for r in h.layer_rows]
+                             for _ in range(nsets)])
+            else:
+                outs.append(torch.empty((nsets, batch, h.rows), dtype=torch.float32, device=dev))
+
+        def run(h, v, o, j, s):
+            if hasattr(h, "layer_rows"):
+                rsr.rsr_matvec_stacked(h, v[0], None, o[j], stream=s)
+            else:
+                rsr.rsr_matvec_ex(h, v, out=o[j], stream=s)
 
         def cold(i, s):
             j = i % nsets
             for h, v, o in zip(sets[j], vs, outs):
-                rsr.rsr_matvec_ex(h, v, out=o[j], stream=s)
+                run(h, v, o, j, s)
 
         def warm(i, s):
             for h, v, o in zip(sets[0], vs, outs):
-                rsr.rsr_matvec_ex(h, v, out=o[0], stream=s)
+                run(h, v, o, 0, s)
 
         tc = time_graph(torch, cold, steps, 50, period=nsets) * 1e3 / steps
         tw = time_graph(torch, warm, steps, 50) * 1e3 / steps
         results.append({"workload": name, "kind": kind_name[kind], "k": k, "batch": batch,
                         "k_used": [h.k for h in sets[0]],
-                        "v_dtype": "bf16" if bf16 else "f32", "layers": len(sets[0]),
+                        "v_dtype": "bf16" if bf16 else "f32", "launches": len(sets[0]),
                         "weight_sets": nsets, "algorithmic_MB": nbytes / 1e6,
                         "cold_us": tc, "warm_us": tw, "cold_GBs": nbytes / tc / 1e3,
                         "kernel": rsr.rsr_kernel_name(sets[0][0], vt)})
@@ -239,10 +256,9 @@ def run_configs(args):
                 for n, l in enumerate(gen.LLM_8B_LAYERS)]
 
     def layers_2b_merged(i):
-        # layers that share their input (q, k, v; gate, up) stacked row-wise: one handle and
-        # one launch each, v staged once
+        # layers that share their input (q, k, v; gate, up) in one stacked handle and one launch each
         m = layers_2b(i)
-        return [np.concatenate(m[0:3]), m[3], np.concatenate(m[4:6]), m[6]]
+        return [m[0:3], m[3], m[4:6], m[6]]
 
     for k in (6, 8, 0):      # k = 0: the library picks k per layer by timing
         one("2B layer set (7 layers)", layers_2b, k, TF, True)

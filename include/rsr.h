@@ -60,14 +60,15 @@ enum {
  *   rows  number of outputs (>= 1); need not be a multiple of k (the last
  *         block is completed with zero rows, whose outputs are never written)
  *   cols  length of v, 1 <= cols <= 32766
- *   k     block height, or 0 to let the library choose (paper, Conclusion: the best
- *         k moves with the device and the matrix shape): it preprocesses with
+ *   k     block height, or 0 to let the library choose (paper, Demonstration Scenarios:
+ *         the best k moves with the device and the matrix shape): it preprocesses with
  *         k = 4, 6, 8, 10, 12 (4..8 for RSR_TERNARY_FUSED), times the multiply kernel of
- *         each on this device with a bf16 vector and keeps the fastest;
+ *         each on this device with both vector types and keeps the fastest;
  *         rsr_block_height() tells the choice.  RSR_BINARY / RSR_TERNARY_2PASS: 1..15;
- *         RSR_TERNARY_FUSED: 1..10; in all cases 4*P + 4*(cols+1) + 9 KiB
- *         must fit the 160 KiB of LDS (P = 2^k or 3^k), else
- *         RSR_EUNSUPPORTED.  Ignored for RSR_DENSE_TERNARY_P2.
+ *         RSR_TERNARY_FUSED: 1..10.  The vector, one float per pattern (P = 2^k or 3^k;
+ *         or, when P is much larger than cols, one float per non-empty pattern of a
+ *         block) and about 10 KiB must fit the 160 KiB of LDS, else RSR_EUNSUPPORTED.
+ *         Ignored for RSR_DENSE_TERNARY_P2.
  *
  * Pattern code of column j in block b: row b*k+r is digit r, least
  * significant first; binary digits {0,1} base 2; fused digits 0,1,2 for
@@ -117,6 +118,32 @@ int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void 
  * here rows <= 32766 (they become the inputs).  Transposes on the GPU, then preprocesses.
  */
 rsr_handle_t rsr_preprocess_transposed(const int8_t *M, int64_t rows, int64_t cols, int k, int kind);
+
+/*
+ * rsr_preprocess_stacked / rsr_matvec_stacked -- sibling layers that share their input
+ * (paper, Kernels Implementation: the Q, K and V projections, and gate and up, are batched
+ * into one operation over a larger pool of row blocks).  One handle over n matrices with
+ * the same `cols`; one launch multiplies them all by the same v, every layer with its own
+ * scale and its own output vector.  No block mixes rows of two layers (each layer is
+ * completed with zero rows to whole blocks), so per layer the canonical artifacts are those
+ * of rsr_preprocess of that layer, block for block: rsr_get_perm / rsr_get_offsets return
+ * the layers' blocks one layer after the other.
+ *
+ *   Ms      HOST array of n DEVICE pointers; Ms[i] is int8 row-major [rows[i]][cols], borrowed
+ *   rows    HOST array of the n row counts (>= 1 each); n <= 8 (RSR_EUNSUPPORTED beyond)
+ *   k, kind as for rsr_preprocess (k = 0: chosen by timing the stacked handle)
+ *   scales  HOST array of n per-layer scales, or NULL for all ones
+ *   outs    HOST array of n DEVICE float32 pointers, outs[i] of length rows[i]; overwritten
+ *
+ * rsr_matvec_stacked is asynchronous on `stream`, allocates nothing (the pointers and
+ * scales travel as kernel arguments) and takes one vector.  rsr_matvec / rsr_matvec_ex,
+ * rsr_serialize and rsr_preprocess_into refuse a stacked handle.
+ */
+rsr_handle_t rsr_preprocess_stacked(const int8_t *const *Ms, const int64_t *rows, int n, int64_t cols,
+                                    int k, int kind);
+int rsr_matvec_stacked(rsr_handle_t h, const void *v, int v_dtype, const float *scales,
+                       void *const *outs, void *stream);
+int rsr_num_layers(rsr_handle_t h);       /* layers of a stacked handle; 0 otherwise */
 
 /*
  * Artifact reuse (paper, System Overview: the matrices are fixed, preprocessing is one-time

@@ -12,4 +12,5 @@ from .binding import (  # noqa: F401
     rsr_error_string, rsr_get_perm, rsr_get_offsets, rsr_get_packed,
     rsr_num_blocks, rsr_block_height, rsr_num_patterns, rsr_num_passes, rsr_algorithmic_bytes,
     rsr_kernel_name, rsr_launch_shape, rsr_probe_empty, rsr_probe_read,
+    rsr_preprocess_stacked, rsr_matvec_stacked,
 )

@@ -24,6 +24,7 @@ exported_symbols = [
     "rsr_num_blocks", "rsr_block_height", "rsr_num_patterns", "rsr_num_passes",
     "rsr_algorithmic_bytes",
     "rsr_kernel_name", "rsr_preprocess_into", "rsr_launch_shape", "rsr_probe_empty", "rsr_probe_read",
+    "rsr_preprocess_stacked", "rsr_matvec_stacked", "rsr_num_layers",
 ]
 
 
@@ -81,6 +82,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.rsr_probe_empty.argtypes = [ci, ci, ci, vp]
     lib.rsr_probe_read.restype = ci
     lib.rsr_probe_read.argtypes = [vp, i64, ci, ci, vp, vp]
+    lib.rsr_preprocess_stacked.restype = vp
+    lib.rsr_preprocess_stacked.argtypes = [vp, vp, ci, i64, ci, ci]
+    lib.rsr_matvec_stacked.restype = ci
+    lib.rsr_matvec_stacked.argtypes = [vp, vp, ci, vp, vp, vp]
+    lib.rsr_num_layers.restype = ci
+    lib.rsr_num_layers.argtypes = [vp]
     lib.rsr_serialized_size.restype = i64
     lib.rsr_serialized_size.argtypes = [vp]
     lib.rsr_serialize.restype = ci
@@ -152,6 +159,42 @@ def rsr_preprocess_transposed(M, k: int, kind: int) -> Handle:
     if not ptr:
         raise RsrError(rsr_last_error(), "rsr_preprocess_transposed")
     return Handle(ptr, cols, rows, int(load_library().rsr_block_height(ptr)), int(kind))
+
+
+def rsr_preprocess_stacked(Ms, k: int, kind: int) -> Handle:
+    """Ms: int8 CUDA tensors [rows_i][cols] that share cols (sibling layers with one input)."""
+    import torch
+    Ms = [M.contiguous() for M in Ms]
+    if not Ms or any(not (M.is_cuda and M.dtype == torch.int8 and M.dim() == 2 and
+                          M.shape[1] == Ms[0].shape[1]) for M in Ms):
+        raise TypeError("Ms must be 2-D int8 CUDA tensors with the same number of columns")
+    n, cols = len(Ms), Ms[0].shape[1]
+    ptrs = (ctypes.c_void_p * n)(*[M.data_ptr() for M in Ms])
+    rows = (ctypes.c_int64 * n)(*[M.shape[0] for M in Ms])
+    with torch.cuda.device(Ms[0].device):
+        torch.cuda.current_stream().synchronize()
+        ptr = load_library().rsr_preprocess_stacked(ptrs, rows, n, cols, int(k), int(kind))
+    if not ptr:
+        raise RsrError(rsr_last_error(), "rsr_preprocess_stacked")
+    h = Handle(ptr, sum(M.shape[0] for M in Ms), cols, int(load_library().rsr_block_height(ptr)), int(kind))
+    h.layer_rows = [M.shape[0] for M in Ms]
+    return h
+
+
+def rsr_matvec_stacked(h: Handle, v, scales=None, outs=None, stream=None):
+    """One launch for all layers of a stacked handle; returns the list of float32 outputs."""
+    import torch
+    n = len(h.layer_rows)
+    if not (v.is_cuda and v.dim() == 1 and v.numel() == h.cols and v.is_contiguous()):
+        raise TypeError("v must be a contiguous CUDA vector of length cols")
+    if outs is None:
+        outs = [torch.empty(r, dtype=torch.float32, device=v.device) for r in h.layer_rows]
+    optr = (ctypes.c_void_p * n)(*[o.data_ptr() for o in outs])
+    sc = (ctypes.c_float * n)(*[float(x) for x in scales]) if scales is not None else None
+    rc = load_library().rsr_matvec_stacked(h.ptr, v.data_ptr(), _dtype_code(v), sc, optr, _stream_ptr(stream))
+    if rc:
+        raise RsrError(rc, "rsr_matvec_stacked")
+    return outs
 
 
 def rsr_preprocess_into(h: Handle, M) -> None:

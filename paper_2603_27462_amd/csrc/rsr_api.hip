@@ -256,46 +256,53 @@ rsr_handle_s *preprocess_with_k(const int8_t *M, int64_t rows, int64_t cols, int
     return h;
 }
 
-// Average duration in microseconds of the multiply kernel of h on a zero bf16 vector
-// (null stream, device buffers supplied by the caller); negative on failure.
+// Average duration in microseconds of the multiply kernel of h on zero vectors (null stream,
+// device buffers supplied by the caller): both vector types, kTimed launches each; negative
+// on failure.
 float time_matvec(rsr_handle_s *h, const void *v, float *out) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     float ms = -1.0f;
-    constexpr int kWarm = 3, kTimed = 10;
+    constexpr int kWarm = 5, kTimed = 60;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto done;
     for (int i = 0; i < kWarm; ++i)
-        if (rsr::launch_rsr_matvec(h, v, RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) != hipSuccess) goto done;
+        if (rsr::launch_rsr_matvec(h, v, i & 1 ? RSR_F32 : RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) !=
+            hipSuccess)
+            goto done;
     if (hipEventRecord(e0, 0) != hipSuccess) goto done;
-    for (int i = 0; i < kTimed; ++i)
-        if (rsr::launch_rsr_matvec(h, v, RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) != hipSuccess) goto done;
+    for (int i = 0; i < 2 * kTimed; ++i)
+        if (rsr::launch_rsr_matvec(h, v, i & 1 ? RSR_F32 : RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) !=
+            hipSuccess)
+            goto done;
     if (hipEventRecord(e1, 0) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) goto done;
     if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) ms = -1.0f;
 done:
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
-    return ms < 0.0f ? -1.0f : ms * 1e3f / kTimed;
+    return ms < 0.0f ? -1.0f : ms * 1e3f / (2 * kTimed);
 }
 
 // k = 0: the block height is a tuning knob whose best value moves with the shape and the
-// device (paper, Conclusion and the k sweep of its interface), so it is chosen by
-// measurement: preprocess with each candidate height, time the multiply kernel, keep
-// the fastest handle.
-rsr_handle_s *preprocess_auto_k(const int8_t *M, int64_t rows, int64_t cols, int kind) {
+// device (paper, Demonstration Scenarios: the best-k comparison across shapes and devices,
+// and the k sweep of its interface), so it is chosen by measurement: preprocess with each
+// candidate height (make(k) returns the handle or null), time the multiply kernel, keep the
+// fastest handle.  padded_rows: an upper bound of the rows of any candidate handle.
+template <typename Make>
+rsr_handle_s *preprocess_auto_k(int kind, int64_t padded_rows, int64_t cols, Make make) {
     static const int fused_k[] = {4, 5, 6, 7, 8};
     static const int binary_k[] = {4, 6, 8, 10, 12};
     const int *cand = (kind == RSR_TERNARY_FUSED) ? fused_k : binary_k;
-    uint16_t *v = nullptr;
+    float *v = nullptr;
     float *out = nullptr;
     rsr_handle_s *best = nullptr;
     float best_us = 0.0f;
     int last_err = RSR_EUNSUPPORTED;
-    if (dev_alloc(&v, (size_t)cols) != hipSuccess || dev_alloc(&out, (size_t)rows) != hipSuccess ||
-        hipMemset(v, 0, (size_t)cols * 2) != hipSuccess) {
+    if (dev_alloc(&v, (size_t)cols) != hipSuccess || dev_alloc(&out, (size_t)padded_rows) != hipSuccess ||
+        hipMemset(v, 0, (size_t)cols * 4) != hipSuccess) {
         (void)hipGetLastError();
         last_err = RSR_ENOMEM;
     } else {
         for (int i = 0; i < 5; ++i) {
-            rsr_handle_s *h = preprocess_with_k(M, rows, cols, cand[i], kind);
+            rsr_handle_s *h = make(cand[i]);
             if (!h) {
                 if (g_last_error != RSR_EUNSUPPORTED) { last_err = g_last_error; break; }
                 continue;
@@ -318,6 +325,41 @@ rsr_handle_s *preprocess_auto_k(const int8_t *M, int64_t rows, int64_t cols, int
     return best;
 }
 
+// Sibling layers stacked row-wise, every layer completed with zero rows to a whole number
+// of units (blocks of k rows / groups of 16 rows), so that no unit mixes two layers.
+rsr_handle_s *preprocess_stacked_with_k(const int8_t *const *Ms, const int64_t *rows, int n, int64_t cols,
+                                        int k, int kind) {
+    const int64_t unit = (kind == RSR_DENSE_TERNARY_P2) ? rsr::kDenseRows : k;
+    int64_t first[rsr::kMaxLayers + 1];
+    first[0] = 0;
+    for (int i = 0; i < n; ++i) first[i + 1] = first[i] + (rows[i] + unit - 1) / unit;
+    const int64_t padded = first[n] * unit;
+    int8_t *T = nullptr;
+    if (dev_alloc(&T, (size_t)(padded * cols)) != hipSuccess) {
+        (void)hipGetLastError();
+        fail(RSR_ENOMEM);
+        return nullptr;
+    }
+    hipError_t e = hipMemsetAsync(T, 0, (size_t)(padded * cols), 0);
+    for (int i = 0; e == hipSuccess && i < n; ++i)
+        e = hipMemcpyAsync(T + first[i] * unit * cols, Ms[i], (size_t)(rows[i] * cols),
+                           hipMemcpyDeviceToDevice, 0);
+    rsr_handle_s *h = nullptr;
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        fail(RSR_EHIP);
+    } else {
+        h = preprocess_with_k(T, padded, cols, k, kind);  // synchronises before returning
+    }
+    (void)hipFree(T);
+    if (h) {
+        h->nlayers = n;
+        for (int i = 0; i < n; ++i) h->layer_rows[i] = rows[i];
+        for (int i = 0; i <= n; ++i) h->layer_first[i] = first[i];
+    }
+    return h;
+}
+
 }  // namespace
 
 extern "C" {
@@ -329,8 +371,60 @@ rsr_handle_t rsr_preprocess(const int8_t *M, int64_t rows, int64_t cols, int k, 
     }
     if (is_rsr_kind(kind) && k < 0) { fail(RSR_EINVAL); return nullptr; }
     if (cols > rsr::kMaxCols || rows > (int64_t)1 << 30) { fail(RSR_EUNSUPPORTED); return nullptr; }
-    if (is_rsr_kind(kind) && k == 0) return preprocess_auto_k(M, rows, cols, kind);
+    if (is_rsr_kind(kind) && k == 0)
+        return preprocess_auto_k(kind, rows, cols,
+                                 [&](int kk) { return preprocess_with_k(M, rows, cols, kk, kind); });
     return preprocess_with_k(M, rows, cols, k, kind);
+}
+
+rsr_handle_t rsr_preprocess_stacked(const int8_t *const *Ms, const int64_t *rows, int n, int64_t cols, int k,
+                                    int kind) {
+    if (!Ms || !rows || n < 1 || cols < 1 || (!is_rsr_kind(kind) && kind != RSR_DENSE_TERNARY_P2) ||
+        (is_rsr_kind(kind) && k < 0)) {
+        fail(RSR_EINVAL);
+        return nullptr;
+    }
+    if (n > rsr::kMaxLayers || cols > rsr::kMaxCols) { fail(RSR_EUNSUPPORTED); return nullptr; }
+    int64_t total = 0;
+    for (int i = 0; i < n; ++i) {
+        if (!Ms[i] || rows[i] < 1) { fail(RSR_EINVAL); return nullptr; }
+        total += rows[i] + 16;
+    }
+    if (total > (int64_t)1 << 30) { fail(RSR_EUNSUPPORTED); return nullptr; }
+    if (is_rsr_kind(kind) && k == 0)
+        return preprocess_auto_k(kind, total, cols, [&](int kk) {
+            return preprocess_stacked_with_k(Ms, rows, n, cols, kk, kind);
+        });
+    return preprocess_stacked_with_k(Ms, rows, n, cols, k, kind);
+}
+
+int rsr_num_layers(rsr_handle_t h) { return good(h) ? h->nlayers : 0; }
+
+int rsr_matvec_stacked(rsr_handle_t h, const void *v, int v_dtype, const float *scales, void *const *outs,
+                       void *stream) {
+    if (!good(h) || h->nlayers < 1 || !v || !outs || (v_dtype != RSR_F32 && v_dtype != RSR_BF16))
+        return fail(RSR_EINVAL);
+    if (h->stale) return fail(RSR_EINVAL);
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return fail(RSR_EHIP);
+    if (device != h->device) return fail(RSR_EINVAL);
+    rsr::LayerTable lt;
+    lt.n = h->nlayers;
+    for (int i = 0; i < rsr::kMaxLayers; ++i) {
+        const bool live = i < h->nlayers;
+        if (live && !outs[i]) return fail(RSR_EINVAL);
+        lt.out[i] = live ? static_cast<float *>(outs[i]) : nullptr;
+        lt.scale[i] = live ? (scales ? scales[i] : 1.0f) : 0.0f;
+        lt.rows[i] = live ? (int)h->layer_rows[i] : 0;
+    }
+    for (int i = 0; i <= rsr::kMaxLayers; ++i)
+        lt.first[i] = (int)h->layer_first[i <= h->nlayers ? i : h->nlayers];
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    const hipError_t e = (h->kind == RSR_DENSE_TERNARY_P2)
+                             ? rsr::launch_dense_matvec(h, v, v_dtype, 1.0f, nullptr, 1, h->cols, h->rows, s, &lt)
+                             : rsr::launch_rsr_matvec(h, v, v_dtype, 1.0f, nullptr, 1, h->cols, h->rows, s, &lt);
+    if (e != hipSuccess) return fail(hip_code(e));
+    return RSR_OK;
 }
 
 rsr_handle_t rsr_preprocess_transposed(const int8_t *M, int64_t rows, int64_t cols, int k, int kind) {
@@ -393,6 +487,7 @@ extern "C" {
 
 int rsr_preprocess_into(rsr_handle_t h, const int8_t *M) {
     if (!good(h) || !M) return fail(RSR_EINVAL);
+    if (h->nlayers > 0) return fail(RSR_EUNSUPPORTED);
     int device = -1;
     if (hipGetDevice(&device) != hipSuccess) return fail(RSR_EHIP);
     if (device != h->device) return fail(RSR_EINVAL);
@@ -499,6 +594,7 @@ extern "C" {
 
 int64_t rsr_serialized_size(rsr_handle_t h) {
     if (!good(h)) { fail(RSR_EINVAL); return -1; }
+    if (h->nlayers > 0) { fail(RSR_EUNSUPPORTED); return -1; }
     int64_t total = (int64_t)sizeof(SerialHeader);
     for (const Piece &pc : pieces_of(h)) total += (int64_t)pc.bytes;
     return total;
@@ -506,6 +602,7 @@ int64_t rsr_serialized_size(rsr_handle_t h) {
 
 int rsr_serialize(rsr_handle_t h, void *host_buf, int64_t capacity) {
     if (!good(h) || !host_buf) return fail(RSR_EINVAL);
+    if (h->nlayers > 0) return fail(RSR_EUNSUPPORTED);
     const int64_t total = rsr_serialized_size(h);
     if (capacity < total) return fail(RSR_EINVAL);
     SerialHeader hd;
@@ -601,6 +698,7 @@ int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void 
     if (!good(h) || !v || !out || batch < 1 || (v_dtype != RSR_F32 && v_dtype != RSR_BF16))
         return fail(RSR_EINVAL);
     if (h->stale) return fail(RSR_EINVAL);  // a failed rsr_preprocess_into left it half-written
+    if (h->nlayers > 0) return fail(RSR_EINVAL);  // stacked handles multiply through rsr_matvec_stacked
     if (batch > 65535) return fail(RSR_EUNSUPPORTED);
     if (batch > 1 && (ldv < h->cols || ldo < h->rows)) return fail(RSR_EINVAL);
     int device = -1;

@@ -134,7 +134,7 @@ template <typename VT, int wpg>
 __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
     const u32x4 *__restrict__ tiled, int ntiles, int slab_tiles, int ngroups, int n_in,
     int n_out, const void *__restrict__ v, long long ldv, int batch, int nv, float *__restrict__ out,
-    long long ldo, float scale) {
+    long long ldo, float scale, const LayerTable layers) {
     constexpr int PLANES = sizeof(VT) == 4 ? 3 : 1;
     constexpr int nthreads = kDenseWaves * 64;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -199,16 +199,28 @@ __global__ __launch_bounds__(kDenseWaves * 64) void k_dense_matvec(
 #pragma unroll
         for (int i = 0; i < wpg; ++i)
             sum += *lds_float(red_at + (uint32_t)(((g * wpg + i) * 16 + n) * 16 + r) * 4u);
-        const long long row = ((long long)blockIdx.x * gpw + g) * kDenseRows + r;
+        const long long group = (long long)blockIdx.x * gpw + g;
+        const long long row = group * kDenseRows + r;
         // the weights were +-2
-        if (n < nvh && row < n_out) out[(long long)(vec0 + n) * ldo + row] = (0.5f * scale) * sum;
+        if (layers.n == 0) {
+            if (n < nvh && row < n_out) out[(long long)(vec0 + n) * ldo + row] = (0.5f * scale) * sum;
+        } else if (n == 0 && row < n_out) {
+            // stacked handle: the group belongs to one layer (layers start on group boundaries)
+            int s_ = 0;
+#pragma unroll
+            for (int i = 1; i < kMaxLayers; ++i)
+                if (i < layers.n && group >= layers.first[i]) s_ = i;
+            const long long local = (group - layers.first[s_]) * kDenseRows + r;
+            if (local < layers.rows[s_]) layers.out[s_][local] = (0.5f * layers.scale[s_]) * sum;
+        }
     }
 }
 
 
 template <typename VT, int WPG>
 hipError_t launch_w(const rsr_handle_s *h, const void *v, float scale, float *out, int batch,
-                    int64_t ldv, int64_t ldo, hipStream_t stream, int nv, int slab_tiles, size_t lds) {
+                    int64_t ldv, int64_t ldo, hipStream_t stream, int nv, int slab_tiles, size_t lds,
+                    const LayerTable &layers) {
     static std::atomic<size_t> enabled[kMaxDevices];
     auto kern = k_dense_matvec<VT, WPG>;
     const int ntiles = (int)(h->row_bytes / (kDenseTileCols / 4));
@@ -220,7 +232,7 @@ hipError_t launch_w(const rsr_handle_s *h, const void *v, float scale, float *ou
                        dim3(kDenseWaves * 64), lds, stream,
                        reinterpret_cast<const u32x4 *>(h->packed), ntiles, slab_tiles, ngroups,
                        (int)h->cols, (int)h->rows, v, (long long)ldv, batch, nv, out, (long long)ldo,
-                       scale);
+                       scale, layers);
     return hipGetLastError();
 }
 
@@ -228,7 +240,7 @@ constexpr size_t kDenseLdsBudget = 150 * 1024;
 
 template <typename VT>
 hipError_t launch(const rsr_handle_s *h, const void *v, float scale, float *out, int batch,
-                  int64_t ldv, int64_t ldo, hipStream_t stream) {
+                  int64_t ldv, int64_t ldo, hipStream_t stream, const LayerTable &layers) {
     const int ntiles = (int)(h->row_bytes / (kDenseTileCols / 4));
     const int planes = sizeof(VT) == 4 ? 3 : 1;
     // vectors per workgroup (the weights are read once for all of them) and the slab of
@@ -246,10 +258,10 @@ hipError_t launch(const rsr_handle_s *h, const void *v, float scale, float *out,
     const size_t lds = (size_t)nv * ((size_t)slab_tiles * kDenseTileCols * 2 * planes + 64) +
                        (size_t)kDenseWaves * 16 * 16 * 4;
     // waves per row group: a power of two, at most one per tile of a slab
-    if (slab_tiles >= 8) return launch_w<VT, 8>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
-    if (slab_tiles >= 4) return launch_w<VT, 4>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
-    if (slab_tiles >= 2) return launch_w<VT, 2>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
-    return launch_w<VT, 1>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds);
+    if (slab_tiles >= 8) return launch_w<VT, 8>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds, layers);
+    if (slab_tiles >= 4) return launch_w<VT, 4>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds, layers);
+    if (slab_tiles >= 2) return launch_w<VT, 2>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds, layers);
+    return launch_w<VT, 1>(h, v, scale, out, batch, ldv, ldo, stream, nv, slab_tiles, lds, layers);
 }
 
 }  // namespace
@@ -266,9 +278,12 @@ hipError_t launch_pack2(const int8_t *M, int64_t rows, int64_t cols, int64_t row
 
 hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale,
                                float *out, int batch, int64_t ldv, int64_t ldo,
-                               hipStream_t stream) {
-    return (v_dtype == RSR_BF16) ? launch<uint16_t>(h, v, scale, out, batch, ldv, ldo, stream)
-                                 : launch<float>(h, v, scale, out, batch, ldv, ldo, stream);
+                               hipStream_t stream, const LayerTable *layers) {
+    LayerTable none;
+    none.n = 0;
+    const LayerTable &lt = layers ? *layers : none;
+    return (v_dtype == RSR_BF16) ? launch<uint16_t>(h, v, scale, out, batch, ldv, ldo, stream, lt)
+                                 : launch<float>(h, v, scale, out, batch, ldv, ldo, stream, lt);
 }
 
 const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype) {

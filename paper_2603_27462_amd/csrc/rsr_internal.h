@@ -19,6 +19,19 @@ constexpr int kLdsBytes = 160 * 1024;  // LDS per workgroup on gfx950
 constexpr int kDenseRows = 16;         // dense comparison kernel: rows per workgroup
 constexpr int kDenseTileCols = 256;    // and columns per 16-byte-per-lane tile
 
+constexpr int kMaxLayers = 8;          // sibling layers one stacked handle can hold
+
+// Kernel argument of a stacked handle: where the rows of every layer go.  A unit is a
+// block of k rows (RSR kinds) or a group of 16 rows (dense kind); layers start on unit
+// boundaries.  n = 0: not stacked.
+struct LayerTable {
+    float *out[kMaxLayers];
+    float scale[kMaxLayers];
+    int first[kMaxLayers + 1];  // first unit of layer i; first[n] = all units
+    int rows[kMaxLayers];
+    int n;
+};
+
 // One pass of an RSR handle (binary, M+, M- or fused).
 //
 // Multiply-kernel stream of a block: in stream order, for every group of identical
@@ -74,6 +87,9 @@ struct rsr_handle_s {
     rsr::FoldShape fold;
     uint32_t *fpack = nullptr;   // by code: scatter-phase weights, four per dword: [k][fold.G][64]
     uint32_t *fshare = nullptr;  // by code: first entry of the level-1 share of every thread [W*64]
+    int nlayers = 0;             // > 0: stacked handle (rows = the layers' rows padded to whole units)
+    int64_t layer_rows[rsr::kMaxLayers] = {};
+    int64_t layer_first[rsr::kMaxLayers + 1] = {};  // first unit (block / group of 16 rows) of a layer
     bool stale = false;          // a failed rsr_preprocess_into left the buffers half-written
     uint8_t *packed = nullptr;   // dense kind: [rows/16][tiles][64 lanes][16 bytes], row_bytes = 64 tiles
     int64_t row_bytes = 0;
@@ -111,10 +127,14 @@ hipError_t launch_pack2(const int8_t *M, int64_t rows, int64_t cols, int64_t row
                         uint8_t *packed, int *err_flag);
 
 // --- multiply launches ---------------------------------------------------------
+// `layers` (may be null): per-layer outputs and scales of a stacked handle; then out, scale
+// and ldo are not used and batch is 1.
 hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale,
-                             float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
+                             float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream,
+                             const LayerTable *layers = nullptr);
 hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale,
-                               float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
+                               float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream,
+                               const LayerTable *layers = nullptr);
 // Writes the name of the multiply kernel h launches for (v_dtype, batch) into buf.
 void rsr_matvec_kernel_name(const rsr_handle_s *h, int v_dtype, char *buf, size_t len);
 const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype);

@@ -68,7 +68,28 @@ struct OutArgs {
     long long ldo;
     int n_out;
     float scale;
+    LayerTable layers;  // stacked handles: per-layer outputs, scales and row counts
 };
+
+// Output rows, rows left and scale of block b: of the matrix, or of the layer the block
+// belongs to.
+__device__ __forceinline__ void block_output(const OutArgs &o, long long b, int k, int vec,
+                                             float **out_rows, long long *rows_left, float *scale) {
+    if (o.layers.n == 0) {
+        *out_rows = o.out + (long long)vec * o.ldo + b * k;
+        *rows_left = (long long)o.n_out - b * k;
+        *scale = o.scale;
+        return;
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxLayers; ++i)
+        if (i < o.layers.n && b >= o.layers.first[i]) s = i;
+    const long long local = (b - o.layers.first[s]) * k;
+    *out_rows = o.layers.out[s] + local;
+    *rows_left = (long long)o.layers.rows[s] - local;
+    *scale = o.layers.scale[s];
+}
 
 // Slabs of the first group a wave requests before v is staged; the others follow the first
 // barrier.  With all four up front the requests for v queue behind 32 KiB of stream per
@@ -507,14 +528,16 @@ __device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
     __syncthreads();
 
     // ---- scatter ----------------------------------------------------------------------------
-    float *out_rows = o.out + (long long)vec * o.ldo + b * f.k;
-    const long long rows_left = (long long)o.n_out - b * f.k;
+    float *out_rows;
+    long long rows_left;
+    float scale;
+    block_output(o, b, f.k, vec, &out_rows, &rows_left, &scale);
     if (BYRANK)
         scatter_by_rank<FIRST>(f, a.gword + b * f.slots, count, sw, prev, e_at, z_at, W, w, lane, tid,
-                               o.scale * a.sign, out_rows, rows_left);
+                               scale * a.sign, out_rows, rows_left);
     else
         scatter_by_code<FIRST, TC>(f, sp, wpre, sw, a.sgn, b, t_at, e_at, c1_at, W, w, lane,
-                                   o.scale * a.sign, out_rows, rows_left);
+                                   scale * a.sign, out_rows, rows_left);
 }
 
 // TC: 0, or the class count of the code-indexed scatter phase when it is the common one
@@ -684,7 +707,8 @@ hipError_t launch_fold_tables(int base, int k, const FoldShape &fs, int W, uint3
 }
 
 hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale,
-                             float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream) {
+                             float *out, int batch, int64_t ldv, int64_t ldo, hipStream_t stream,
+                             const LayerTable *layers) {
     LaunchArgs x;
     const FoldShape &fs = h->fold;
     PassArgs *pa[2] = {&x.a0, &x.a1};
@@ -722,6 +746,10 @@ hipError_t launch_rsr_matvec(const rsr_handle_s *h, const void *v, int v_dtype, 
     x.o.ldo = ldo;
     x.o.n_out = (int)h->rows;
     x.o.scale = scale;
+    if (layers)
+        x.o.layers = *layers;
+    else
+        x.o.layers.n = 0;
     x.lds = (size_t)matvec_lds_bytes(h->slots, h->cols, (v_dtype == RSR_BF16) ? 2 : 4, h->W,
                                      h->by_rank != 0);
     x.stream = stream;

@@ -1,5 +1,5 @@
 """A torch module around one RSR handle (the role the paper gives its RSRLinear layer in
-Model Integration: a drop-in for a ternary linear layer whose weight is fixed after
+System Overview, "Integration": a drop-in for a ternary linear layer whose weight is fixed after
 preprocessing).  Argument marshalling only: the product runs in librsr."""
 from __future__ import annotations
 

@@ -246,6 +246,46 @@ def test_transposed_handle(kind, k):
     _check_matvec(h, Mt, rows, 12)
 
 
+@pytest.mark.parametrize("kind,k", [(rsr.RSR_TERNARY_FUSED, 6), (rsr.RSR_TERNARY_FUSED, 0),
+                                    (rsr.RSR_TERNARY_2PASS, 5), (rsr.RSR_BINARY, 8),
+                                    (rsr.RSR_TERNARY_FUSED, 10), (rsr.RSR_DENSE_TERNARY_P2, 0)])
+def test_stacked_sibling_layers(kind, k):
+    """Layers that share their input in one handle and one launch: per layer the artifacts are
+    those of the layer alone, block for block, and the outputs (own scale, own vector) are the
+    dense products; nothing is written behind a layer's rows."""
+    cols, rows = 640, [96, 41, 33]
+    Ms = [_matrix(kind, r, cols, 400 + r) for r in rows]
+    h = rsr.rsr_preprocess_stacked([_dev(M) for M in Ms], k, kind)
+    kk = h.k
+    if kind != rsr.RSR_DENSE_TERNARY_P2:
+        arts = [oracle.preprocess(M, kk, KINDS[kind]) for M in Ms]
+        for ps in range(rsr.rsr_num_passes(h)):
+            pi, off = rsr.rsr_get_perm(h, ps), rsr.rsr_get_offsets(h, ps)
+            b0 = 0
+            for art in arts:
+                nb = art.passes[ps].pi.shape[0]
+                assert np.array_equal(pi[b0:b0 + nb], art.passes[ps].pi)
+                assert np.array_equal(off[b0:b0 + nb], art.passes[ps].off)
+                b0 += nb
+            assert b0 == pi.shape[0]
+    scales = [0.5, 2.0, -1.25]
+    vi = gen.integer_f32(cols, seed=77)
+    outs = [torch.full((r + 5,), 9.0, dtype=torch.float32, device=DEV) for r in rows]
+    rsr.rsr_matvec_stacked(h, _dev(vi), scales, [o[:r] for o, r in zip(outs, rows)])
+    for M, sc, o, r in zip(Ms, scales, outs, rows):
+        got = o.cpu().numpy()
+        assert np.all(got[r:] == 9.0)
+        assert np.array_equal(got[:r].astype(np.float64), oracle.dense_matvec(M, vi.astype(np.float64), sc))
+    bits, vals = gen.normal_bf16(cols, seed=78)
+    got = rsr.rsr_matvec_stacked(h, _bf16_dev(bits), scales)
+    for M, sc, o in zip(Ms, scales, got):
+        want = oracle.dense_matvec(M, vals.astype(np.float64), sc)
+        assert np.max(np.abs(o.cpu().numpy() - want)) <= _tol(vals, sc)
+    with pytest.raises(rsr.RsrError):
+        rsr.rsr_matvec(h, _dev(vi))            # a stacked handle has no single output vector
+    rsr.rsr_destroy(h)
+
+
 def test_linear_module():
     from paper_2603_27462_amd.linear import RsrLinear
     rows, cols = 96, 640
