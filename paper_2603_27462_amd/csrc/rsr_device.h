@@ -64,24 +64,41 @@ __device__ __forceinline__ uint32_t entry_addr(uint32_t d) {
     return HALF ? ((d >> 15) & 0x1fffcu) : ((d & 0xfffeu) << 1);
 }
 
-// Gather one element of v as float bits.  For bf16 the 16 bits land in the high
-// half of g, whose low half is zero and stays zero (g is only ever written here).
+// Gathers eight elements of v as float bits and waits for them, in one instruction block:
+// the compiler does not see the LDS operations, and between a read it does not know of and
+// the wait for it, it would be free to copy the destination register while the data is still
+// on its way.  For bf16 the 16 bits land in the high half of g[i], whose low half is zero
+// and stays zero (g is only ever written here).
 template <typename VT>
-__device__ __forceinline__ void gather(uint32_t &g, uint32_t addr) {
+__device__ __forceinline__ void gather8(uint32_t (&g)[8], const uint32_t (&a)[8]) {
     if (sizeof(VT) == 4)
-        asm volatile("ds_read_b32 %0, %1" : "=v"(g) : "v"(addr));
+        asm volatile(
+            "ds_read_b32 %0, %8\n\t"
+            "ds_read_b32 %1, %9\n\t"
+            "ds_read_b32 %2, %10\n\t"
+            "ds_read_b32 %3, %11\n\t"
+            "ds_read_b32 %4, %12\n\t"
+            "ds_read_b32 %5, %13\n\t"
+            "ds_read_b32 %6, %14\n\t"
+            "ds_read_b32 %7, %15\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]), "+v"(g[4]), "+v"(g[5]), "+v"(g[6]), "+v"(g[7])
+            : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7])
+            : "memory");
     else
-        asm volatile("ds_read_u16_d16_hi %0, %1" : "+v"(g) : "v"(addr));
-}
-
-// Wait until at most N of the LDS operations issued so far are outstanding; the
-// eight registers are the results the caller is about to read.
-template <int N>
-__device__ __forceinline__ void lds_wait(uint32_t (&g)[8]) {
-    asm volatile("s_waitcnt lgkmcnt(%8)"
-                 : "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]), "+v"(g[4]), "+v"(g[5]),
-                   "+v"(g[6]), "+v"(g[7])
-                 : "n"(N));
+        asm volatile(
+            "ds_read_u16_d16_hi %0, %8\n\t"
+            "ds_read_u16_d16_hi %1, %9\n\t"
+            "ds_read_u16_d16_hi %2, %10\n\t"
+            "ds_read_u16_d16_hi %3, %11\n\t"
+            "ds_read_u16_d16_hi %4, %12\n\t"
+            "ds_read_u16_d16_hi %5, %13\n\t"
+            "ds_read_u16_d16_hi %6, %14\n\t"
+            "ds_read_u16_d16_hi %7, %15\n\t"
+            "s_waitcnt lgkmcnt(0)"
+            : "+v"(g[0]), "+v"(g[1]), "+v"(g[2]), "+v"(g[3]), "+v"(g[4]), "+v"(g[5]), "+v"(g[6]), "+v"(g[7])
+            : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7])
+            : "memory");
 }
 
 // The two entries of dword d: if an entry is a tail, E[ptr] = s, ptr += 4.

@@ -199,9 +199,13 @@ __device__ __forceinline__ uint32_t load_sign_word(const void *sgn, long long in
                   : static_cast<const uint32_t *>(sgn)[index];
 }
 
+constexpr int kMoreRows = 3;  // further rows of a wave (w + W, w + 2W, ...) whose tables are requested up front
+
 template <bool FIRST, int TC>
 __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const ScatterPrep &sp,
-                                                uint32_t wpre, uint32_t sw, const void *sgn,
+                                                uint32_t wpre, uint32_t sw,
+                                                const uint32_t (&pk_more)[kMoreRows],
+                                                const uint32_t (&sw_more)[kMoreRows], const void *sgn,
                                                 long long b, uint32_t t_at, uint32_t e_at,
                                                 uint32_t c1_at, int W, int w, int lane,
                                                 float sign_scale, float *out_rows,
@@ -211,32 +215,40 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
         // by one (wave-uniform branches; the loads of a batch are in flight together)
         const uint32_t step = class_step<TC>(f);
         float x[kL1Regs];
-#pragma unroll
-        for (int i = 0; i < kL1Regs; ++i) x[i] = 0.0f;
-        const int n1 = f.cnt1 < kL1Regs ? f.cnt1 : kL1Regs;
-#pragma unroll
-        for (int i0 = 0; i0 < kL1Regs; i0 += 4) {
-            if (i0 + 4 <= n1) {
-#pragma unroll
-                for (int i = i0; i < i0 + 4; ++i) x[i] = *lds_float(sp.first + (uint32_t)i * step);
-            } else {
-#pragma unroll
-                for (int i = i0; i < i0 + 3; ++i)
-                    if (i < n1) x[i] = *lds_float(sp.first + (uint32_t)i * step);
-            }
-        }
         float rest = 0.0f;
-        if (f.cnt1 > kL1Regs) {
-            uint32_t at = sp.first + (uint32_t)kL1Regs * step;
-            for (int i = kL1Regs; i < f.cnt1; ++i) {
-                rest += *lds_float(at);
-                at += step;
+        if (f.cnt1 <= 4) {
+            // short shares: entries past the share read E[0], which is zero (no branches)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                x[i] = *lds_float(i < f.cnt1 ? sp.first + (uint32_t)i * step : e_at);
+            x[0] = (x[0] + x[1]) + (x[2] + x[3]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kL1Regs; ++i) x[i] = 0.0f;
+            const int n1 = f.cnt1 < kL1Regs ? f.cnt1 : kL1Regs;
+#pragma unroll
+            for (int i0 = 0; i0 < kL1Regs; i0 += 4) {
+                if (i0 + 4 <= n1) {
+#pragma unroll
+                    for (int i = i0; i < i0 + 4; ++i) x[i] = *lds_float(sp.first + (uint32_t)i * step);
+                } else {
+#pragma unroll
+                    for (int i = i0; i < i0 + 3; ++i)
+                        if (i < n1) x[i] = *lds_float(sp.first + (uint32_t)i * step);
+                }
             }
+            if (f.cnt1 > kL1Regs) {
+                uint32_t at = sp.first + (uint32_t)kL1Regs * step;
+                for (int i = kL1Regs; i < f.cnt1; ++i) {
+                    rest += *lds_float(at);
+                    at += step;
+                }
+            }
+#pragma unroll
+            for (int d = 1; d < kL1Regs; d *= 2)
+#pragma unroll
+                for (int i = 0; i + d < kL1Regs; i += 2 * d) x[i] += x[i + d];
         }
-#pragma unroll
-        for (int d = 1; d < kL1Regs; d *= 2)
-#pragma unroll
-            for (int i = 0; i + d < kL1Regs; i += 2 * d) x[i] += x[i + d];
         const float col = x[0] + rest;
         *lds_float(sp.c1_store) = col;
     }
@@ -266,7 +278,8 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
         }
         return;
     }
-    for (int r = w; r < f.k; r += W) {
+    int turn = 0;
+    for (int r = w; r < f.k; r += W, ++turn) {
         const bool low = r < f.m;
         const int n = low ? f.Tc : f.Q;
         // element j of the row: class sum C1[0][j] (+ C1[1][j]), or E[Tc j + Tc - 1]
@@ -274,10 +287,17 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
         const uint32_t stride = low ? 4u : class_step<TC>(f);
         const bool two = low && f.parts == 2;
         const uint32_t second = class_step<TC>(f);
-        const uint32_t swr = (r == w) ? sw : load_sign_word(sgn, (b * f.k + r) * 64 + lane, W);
+        uint32_t swr = sw, pk0 = wpre;
+        if (turn == 1) { swr = sw_more[0]; pk0 = pk_more[0]; }
+        if (turn == 2) { swr = sw_more[1]; pk0 = pk_more[1]; }
+        if (turn == 3) { swr = sw_more[2]; pk0 = pk_more[2]; }
+        if (turn > kMoreRows) {
+            swr = load_sign_word(sgn, (b * f.k + r) * 64 + lane, W);
+            pk0 = f.fpack[(r * f.G) * 64 + lane];
+        }
         float x = strip_terms(sp, swr, W);
         for (int g = 0; g * 256 < n; ++g) {
-            const uint32_t pk = (r == w && g == 0) ? wpre : f.fpack[(r * f.G + g) * 64 + lane];
+            const uint32_t pk = (g == 0) ? pk0 : f.fpack[(r * f.G + g) * 64 + lane];
             const int j0 = lane + 256 * g;
             // the four loads first, then the arithmetic (entries past n have weight 0)
             const uint32_t a0 = base + stride * (uint32_t)min(j0, n - 1);
@@ -352,23 +372,19 @@ __device__ __forceinline__ void scatter_by_rank(const FoldArgs &f, const uint32_
 }
 
 // ---- gather + aggregate: one slab of a wave -----------------------------------------------
-// Eight entries per lane: gather the eight elements of v (slab_gather), then extend the
-// strip's running sum and let every tail store its prefix (slab_finish).  NEWER: LDS
-// operations issued after the gathers that may still be outstanding when they are used.
+// Eight entries per lane: gather the eight elements of v, extend the strip's running sum,
+// and let every tail store its prefix.
 template <typename VT, int ENC>
-__device__ __forceinline__ void slab_gather(const u32x4 &q, uint32_t (&g)[8]) {
+__device__ __forceinline__ void slab_step(const u32x4 &q, uint32_t (&g)[8], float &prev,
+                                          uint32_t &ptr) {
     const uint32_t d[4] = {q.x, q.y, q.z, q.w};
+    uint32_t a[8];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        gather<VT>(g[2 * j], entry_addr<VT, ENC, 0>(d[j]));
-        gather<VT>(g[2 * j + 1], entry_addr<VT, ENC, 1>(d[j]));
+        a[2 * j] = entry_addr<VT, ENC, 0>(d[j]);
+        a[2 * j + 1] = entry_addr<VT, ENC, 1>(d[j]);
     }
-}
-
-template <int ENC, int NEWER>
-__device__ __forceinline__ void slab_finish(const u32x4 &q, uint32_t (&g)[8], float &prev,
-                                            uint32_t &ptr) {
-    lds_wait<NEWER>(g);
+    gather8<VT>(g, a);
     float s[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
@@ -376,12 +392,10 @@ __device__ __forceinline__ void slab_finish(const u32x4 &q, uint32_t (&g)[8], fl
         s[i] = prev;
     }
     if (ENC == kEncSmall) {
-        tail_store8_small(q.x, q.y, q.z, q.w, s, ptr);
+        tail_store8_small(d[0], d[1], d[2], d[3], s, ptr);
     } else {
-        tail_store2_big(q.x, s[0], s[1], ptr);
-        tail_store2_big(q.y, s[2], s[3], ptr);
-        tail_store2_big(q.z, s[4], s[5], ptr);
-        tail_store2_big(q.w, s[6], s[7], ptr);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) tail_store2_big(d[j], s[2 * j], s[2 * j + 1], ptr);
     }
 }
 
@@ -405,15 +419,15 @@ __device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
     const int nthreads = W * 64;
     const long long b = blockIdx.x;
 
-    // the wave's slabs, in groups of four; the first group may be short at its front
+    // the wave's slabs, in groups of four; the first group may be short (n0 slabs)
     const int n_w = per + (w < rem ? 1 : 0);
     const int first = w * per + min(w, rem);
     const int ngroups = (n_w + kGroupSlabs - 1) / kGroupSlabs;
-    const int lead = ngroups * kGroupSlabs - n_w;  // absent slots of the first group
+    const int n0 = n_w - (ngroups - 1) * kGroupSlabs;
 
     // ---- the global loads of the pass, in the order of use: v (the first barrier waits for
-    // it), the strip's first slot and the first slabs; behind the first barrier the small
-    // tables of the scatter phase and the remaining slabs ---------------------------------
+    // it), the strip's first slot, the first slabs and the small tables of the scatter phase;
+    // behind the first barrier the remaining slabs ------------------------------------------
     const long long vstride = ldv * (long long)sizeof(VT);
     const unsigned char *vg = reinterpret_cast<const unsigned char *>(v) + (long long)vec * vstride;
     const int nbytes = n_in * (int)sizeof(VT);
@@ -432,15 +446,16 @@ __device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
     }
     const uint32_t slot0 = __builtin_nontemporal_load(&start[(b * W + w) * 64 + lane]);
     // The stream is read once: non-temporal loads keep it out of the way of v and the
-    // tables.  Slots without a slab (the front of the first group, waves without slabs)
+    // tables.  Slots without a slab (the end of a short first group, waves without slabs)
     // repeat a neighbouring slab and are ignored: no branch, so nothing delays the requests
     // and the number of loads in flight is the same in every wave.
     const u32x4 *ep = reinterpret_cast<const u32x4 *>(entries) + (b * S) * 64 + lane;
     u32x4 q[kGroupSlabs];
 #pragma unroll
     for (int j = 0; j < kEarlySlabs; ++j)
-        q[j] = __builtin_nontemporal_load(&ep[(long long)min(first + max(j - lead, 0), S - 1) * 64]);
+        q[j] = __builtin_nontemporal_load(&ep[(long long)min(first + min(j, n0 - 1), S - 1) * 64]);
     uint32_t share = 0, wpre = 0, sw = 0, count = 0;
+    uint32_t pk_more[kMoreRows] = {0, 0, 0}, sw_more[kMoreRows] = {0, 0, 0};
     auto load_tables = [&]() {
         if (BYRANK) {
             sw = static_cast<const uint32_t *>(a.sgn)[(b * W + w) * 64 + lane];
@@ -449,9 +464,17 @@ __device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
             share = f.fshare[tid];
             wpre = f.fpack[(min(w, f.k - 1) * f.G) * 64 + lane];
             sw = load_sign_word(a.sgn, (b * f.k + min(w, f.k - 1)) * 64 + lane, W);
+            if (f.k > W) {  // fewer waves than rows: the tables of the wave's further rows
+#pragma unroll
+                for (int i = 0; i < kMoreRows; ++i) {
+                    const int r = min(w + (i + 1) * W, f.k - 1);
+                    pk_more[i] = f.fpack[(r * f.G) * 64 + lane];
+                    sw_more[i] = load_sign_word(a.sgn, (b * f.k + r) * 64 + lane, W);
+                }
+            }
         }
     };
-    if (kEarlySlabs == kGroupSlabs) load_tables();
+    load_tables();
 
     // ---- stage v -----------------------------------------------------------------------------
     if (FIRST) {
@@ -476,11 +499,11 @@ __device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
     ScatterPrep sp;
     if (kEarlySlabs == kGroupSlabs && !BYRANK)
         prepare_scatter<TC>(sp, f, share, wpre, t_at, e_at, c1_at, W, w, lane, tid);
-    uint32_t g[2][8];  // gather targets: for bf16 the low halves must be zero
+    uint32_t g[8];  // gather targets: for bf16 the low halves must be zero
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        g[i >> 3][i & 7] = 0u;
-        pin(g[i >> 3][i & 7]);
+    for (int i = 0; i < 8; ++i) {
+        g[i] = 0u;
+        pin(g[i]);
     }
     if (!BYRANK) {
         if (tid < (TC > 0 ? TC : f.Tc)) *lds_float(z_at + (uint32_t)tid * 4u) = 0.0f;
@@ -490,35 +513,24 @@ __device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
     if (tid == 0) *lds_float(e_at) = 0.0f;
     __syncthreads();
     if (kEarlySlabs < kGroupSlabs) {
-        load_tables();
 #pragma unroll
         for (int j = kEarlySlabs; j < kGroupSlabs; ++j)
-            q[j] = __builtin_nontemporal_load(&ep[(long long)min(first + max(j - lead, 0), S - 1) * 64]);
+            q[j] = __builtin_nontemporal_load(&ep[(long long)min(first + min(j, n0 - 1), S - 1) * 64]);
     }
 
-    // ---- gather + aggregate, slab by slab as the loads return: the gathers of a slab are
-    // issued before the previous slab's sums and tail stores, so that the LDS always has
-    // reads queued while the wave computes ---------------------------------------------------
+    // ---- gather + aggregate, slab by slab as the loads return ------------------------------
     float prev = 0.0f;
     uint32_t ptr = e_at + slot0 * 4u;
     if (ngroups > 0) {
-        // (lead < kGroupSlabs: the last slot always holds a slab)
 #pragma unroll
-        for (int j = 0; j < kGroupSlabs; ++j) {
-            if (j >= lead) slab_gather<VT, ENC>(q[j], g[j & 1]);
-            if (j >= 1 && j - 1 >= lead) slab_finish<ENC, 8>(q[j - 1], g[(j - 1) & 1], prev, ptr);
-        }
-        slab_finish<ENC, 0>(q[kGroupSlabs - 1], g[(kGroupSlabs - 1) & 1], prev, ptr);
+        for (int j = 0; j < kGroupSlabs; ++j)
+            if (j < n0) slab_step<VT, ENC>(q[j], g, prev, ptr);
         for (int grp = 1; grp < ngroups; ++grp) {
-            const u32x4 *gp = ep + (long long)(first + grp * kGroupSlabs - lead) * 64;
+            const u32x4 *gp = ep + (long long)(first + n0 + (grp - 1) * kGroupSlabs) * 64;
 #pragma unroll
             for (int j = 0; j < kGroupSlabs; ++j) q[j] = __builtin_nontemporal_load(&gp[j * 64]);
 #pragma unroll
-            for (int j = 0; j < kGroupSlabs; ++j) {
-                slab_gather<VT, ENC>(q[j], g[j & 1]);
-                if (j >= 1) slab_finish<ENC, 8>(q[j - 1], g[(j - 1) & 1], prev, ptr);
-            }
-            slab_finish<ENC, 0>(q[kGroupSlabs - 1], g[(kGroupSlabs - 1) & 1], prev, ptr);
+            for (int j = 0; j < kGroupSlabs; ++j) slab_step<VT, ENC>(q[j], g, prev, ptr);
         }
     }
     if (kEarlySlabs < kGroupSlabs && !BYRANK)
@@ -536,7 +548,7 @@ __device__ __forceinline__ void run_pass(const uint16_t *__restrict__ entries,
         scatter_by_rank<FIRST>(f, a.gword + b * f.slots, count, sw, prev, e_at, z_at, W, w, lane, tid,
                                scale * a.sign, out_rows, rows_left);
     else
-        scatter_by_code<FIRST, TC>(f, sp, wpre, sw, a.sgn, b, t_at, e_at, c1_at, W, w, lane,
+        scatter_by_code<FIRST, TC>(f, sp, wpre, sw, pk_more, sw_more, a.sgn, b, t_at, e_at, c1_at, W, w, lane,
                                    scale * a.sign, out_rows, rows_left);
 }
 
