@@ -47,6 +47,11 @@ def parse_args():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain device copy of 256 MiB (a kernel of known traffic, "
                          "to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--max-sets", type=int, default=40, help="with --configs: weight sets per workload at most")
+    ap.add_argument("--no-auto-k", action="store_true", help="with --configs: skip the lines where the "
+                                                             "library chooses k (many extra launches)")
+    ap.add_argument("--only", default="", help="with --configs: run only the workloads whose name "
+                                               "contains this text")
     ap.add_argument("--configs", action="store_true",
                     help="instead of the metric line: time the other workload families (binary "
                          "1024^2, ternary 4096^2 over k, the 2B and 8B layer sets, the retrieval "
@@ -182,6 +187,10 @@ def run_configs(args):
         """make_layers(set_index) -> list of int8 matrices (numpy); an entry that is itself a
         list is a group of sibling layers (same input) served by one stacked handle."""
         vt = rsr.RSR_BF16 if bf16 else rsr.RSR_F32
+        if (args.only and args.only not in name) or (args.no_auto_k and k == 0 and kind != D):
+            return
+        max_sets = min(max_sets, args.max_sets)
+        print("  ... %s %s k=%d batch=%d" % (name, kind_name[kind], k, batch), file=sys.stderr, flush=True)
 
         def prep(M):
             if isinstance(M, list):

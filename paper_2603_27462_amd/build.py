@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "librsr.so")
-SOURCES = ["rsr_api.hip", "rsr_preprocess.hip", "rsr_matvec.hip", "rsr_dense.hip", "rsr_probe.hip"]
+SOURCES = ["rsr_api.hip", "rsr_preprocess.hip", "rsr_matvec.hip", "rsr_dense.hip", "rsr_probe.hip", "rsr_narrow.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

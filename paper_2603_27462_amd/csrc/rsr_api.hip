@@ -36,6 +36,9 @@ void free_handle(rsr_handle_s *h) {
         if (ps.start) (void)hipFree(ps.start);
         if (ps.sgn) (void)hipFree(ps.sgn);
         if (ps.gword) (void)hipFree(ps.gword);
+        if (ps.nent) (void)hipFree(ps.nent);
+        if (ps.nmeta) (void)hipFree(ps.nmeta);
+        if (ps.nsw) (void)hipFree(ps.nsw);
         if (ps.gcount) (void)hipFree(ps.gcount);
     }
     if (h->fpack) (void)hipFree(h->fpack);
@@ -128,6 +131,12 @@ int64_t slabs_for(int64_t entries) {
 // the stream and the small tables of the multiply kernel, in the layout the handle records
 int run_pack_passes(rsr_handle_s *h, const Temps &t) {
     int host[kFlagWords];
+    if (h->narrow) {
+        for (int ps = 0; ps < h->npass; ++ps)
+            if (rsr::launch_pack_narrow(h, ps, t.flags + kFlagErr) != hipSuccess) return RSR_EHIP;
+        if (int rc = read_flags(t, host)) return rc;
+        return host[kFlagErr] ? RSR_EINTERNAL : RSR_OK;
+    }
     if (!h->by_rank &&
         rsr::launch_fold_tables(h->base, h->k, h->fold, h->W, h->fpack, h->fshare) != hipSuccess)
         return RSR_EHIP;
@@ -159,7 +168,7 @@ done:
     return rc;
 }
 
-int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
+int preprocess_rsr(rsr_handle_s *h, const int8_t *M, bool allow_narrow) {
     int rc = RSR_OK;
     Temps t;
     const int64_t nb = h->nb, cols = h->cols, P = h->P;
@@ -172,6 +181,26 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M) {
         RSR_TRY(dev_alloc(&h->pass[ps].off, (size_t)(nb * (P + 1))));
     }
     if ((rc = run_sort_passes(h, M, t, &st)) != RSR_OK) goto done;
+    {
+        // narrow matrices: 8-bit entries, one wave per block
+        const int fw = h->base == 2 ? 1 : 2;
+        if (allow_narrow && cols <= rsr::kNarrowCols && h->k * fw <= 32) {
+            int64_t most = st.groups[0] > st.groups[1] ? st.groups[0] : st.groups[1];
+            h->narrow = 1;
+            h->narrow_fw = fw;
+            h->narrow_sw_bytes = h->k * fw <= 8 ? 1 : h->k * fw <= 16 ? 2 : 4;
+            h->slots = most < 4 ? 4 : (most + 3) / 4 * 4;
+            for (int ps = 0; ps < h->npass; ++ps) {
+                rsr::PassData &pd = h->pass[ps];
+                RSR_TRY(dev_alloc(&pd.nent, (size_t)nb * 64));
+                RSR_TRY(dev_alloc(&pd.nmeta, (size_t)nb * 64));
+                RSR_TRY(dev_alloc(reinterpret_cast<unsigned char **>(&pd.nsw),
+                                  (size_t)(nb * h->slots) * h->narrow_sw_bytes));
+            }
+            rc = run_pack_passes(h, t);
+            goto done;
+        }
+    }
     {
         const int ph = (h->npass == 2 && st.with_empty[1] > st.with_empty[0]) ? 1 : 0;  // the heavier pass
         h->by_rank = rsr::choose_by_rank(P, cols, st.with_empty[ph], st.real[ph], st.groups[ph]) ? 1 : 0;
@@ -222,7 +251,8 @@ done:
 namespace {
 
 // Preprocessing with a given block height (k is ignored for the dense kind).
-rsr_handle_s *preprocess_with_k(const int8_t *M, int64_t rows, int64_t cols, int k, int kind) {
+rsr_handle_s *preprocess_with_k(const int8_t *M, int64_t rows, int64_t cols, int k, int kind,
+                                bool allow_narrow = true) {
     rsr_handle_s *h = new (std::nothrow) rsr_handle_s();
     if (!h) { fail(RSR_ENOMEM); return nullptr; }
     h->magic = rsr::kMagic;
@@ -243,7 +273,7 @@ rsr_handle_s *preprocess_with_k(const int8_t *M, int64_t rows, int64_t cols, int
         if (k > kmax) { free_handle(h); fail(RSR_EUNSUPPORTED); return nullptr; }
         h->P = ipow(h->base, k);
         h->nb = (rows + k - 1) / k;
-        rc = preprocess_rsr(h, M);
+        rc = preprocess_rsr(h, M, allow_narrow);
     }
     if (rc == RSR_OK && hipDeviceSynchronize() != hipSuccess) rc = RSR_EHIP;
     if (rc != RSR_OK) {
@@ -256,6 +286,11 @@ rsr_handle_s *preprocess_with_k(const int8_t *M, int64_t rows, int64_t cols, int
     return h;
 }
 
+hipError_t launch_any(rsr_handle_s *h, const void *v, int v_dtype, float *out) {
+    return h->narrow ? rsr::launch_narrow_matvec(h, v, v_dtype, 1.0f, out, 1, h->cols, h->rows, 0)
+                     : rsr::launch_rsr_matvec(h, v, v_dtype, 1.0f, out, 1, h->cols, h->rows, 0);
+}
+
 // Average duration in microseconds of the multiply kernel of h on zero vectors (null stream,
 // device buffers supplied by the caller): both vector types, kTimed launches each; negative
 // on failure.
@@ -265,14 +300,10 @@ float time_matvec(rsr_handle_s *h, const void *v, float *out) {
     constexpr int kWarm = 5, kTimed = 60;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) goto done;
     for (int i = 0; i < kWarm; ++i)
-        if (rsr::launch_rsr_matvec(h, v, i & 1 ? RSR_F32 : RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) !=
-            hipSuccess)
-            goto done;
+        if (launch_any(h, v, i & 1 ? RSR_F32 : RSR_BF16, out) != hipSuccess) goto done;
     if (hipEventRecord(e0, 0) != hipSuccess) goto done;
     for (int i = 0; i < 2 * kTimed; ++i)
-        if (rsr::launch_rsr_matvec(h, v, i & 1 ? RSR_F32 : RSR_BF16, 1.0f, out, 1, h->cols, h->rows, 0) !=
-            hipSuccess)
-            goto done;
+        if (launch_any(h, v, i & 1 ? RSR_F32 : RSR_BF16, out) != hipSuccess) goto done;
     if (hipEventRecord(e1, 0) != hipSuccess || hipEventSynchronize(e1) != hipSuccess) goto done;
     if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) ms = -1.0f;
 done:
@@ -349,7 +380,8 @@ rsr_handle_s *preprocess_stacked_with_k(const int8_t *const *Ms, const int64_t *
         (void)hipGetLastError();
         fail(RSR_EHIP);
     } else {
-        h = preprocess_with_k(T, padded, cols, k, kind);  // synchronises before returning
+        // (the narrow kernel writes one output vector: stacked handles take the general one)
+        h = preprocess_with_k(T, padded, cols, k, kind, false);  // synchronises before returning
     }
     (void)hipFree(T);
     if (h) {
@@ -509,8 +541,10 @@ int rsr_preprocess_into(rsr_handle_t h, const int8_t *M) {
             if (h->pass[ps].S > maxS) maxS = h->pass[ps].S;
         t.code = reinterpret_cast<uint16_t *>(base + at);
         at += align256((size_t)(h->nb * h->cols) * sizeof(uint16_t));
-        t.logical = reinterpret_cast<uint16_t *>(base + at);
-        at += align256((size_t)(h->nb * maxS * rsr::kSlab) * sizeof(uint16_t));
+        if (!h->narrow) {
+            t.logical = reinterpret_cast<uint16_t *>(base + at);
+            at += align256((size_t)(h->nb * maxS * rsr::kSlab) * sizeof(uint16_t));
+        }
         if (h->by_rank) {
             t.gcode = reinterpret_cast<uint16_t *>(base + at);
             at += align256((size_t)(h->nb * h->slots) * sizeof(uint16_t));
@@ -522,7 +556,8 @@ int rsr_preprocess_into(rsr_handle_t h, const int8_t *M) {
         for (int ps = 0; rc == RSR_OK && ps < h->npass; ++ps) {
             // the new matrix has to fit the layout the handle was allocated for
             const int64_t need = h->by_rank ? st.real[ps] : st.with_empty[ps];
-            if (need > h->pass[ps].S * rsr::kSlab || (h->by_rank && st.groups[ps] + 1 > h->slots))
+            if (h->narrow ? st.groups[ps] > h->slots
+                          : (need > h->pass[ps].S * rsr::kSlab || (h->by_rank && st.groups[ps] + 1 > h->slots)))
                 rc = RSR_EUNSUPPORTED;
         }
         if (rc == RSR_OK) rc = run_pack_passes(h, t);
@@ -548,7 +583,7 @@ constexpr uint32_t kSerialVersion = 2;
 
 struct SerialHeader {
     uint32_t magic, version;
-    int32_t kind, k, base, npass, W, by_rank, enc, reserved;
+    int32_t kind, k, base, npass, W, by_rank, enc, narrow;
     int64_t rows, cols, nb, P, row_bytes;
     int64_t S[2];
     int64_t slots;
@@ -573,6 +608,12 @@ std::vector<Piece> pieces_of(rsr_handle_s *h) {
         rsr::PassData &pd = h->pass[ps];
         p.push_back({reinterpret_cast<void **>(&pd.pi), (size_t)(h->nb * h->cols) * 2});
         p.push_back({reinterpret_cast<void **>(&pd.off), (size_t)(h->nb * (h->P + 1)) * 4});
+        if (h->narrow) {
+            p.push_back({reinterpret_cast<void **>(&pd.nent), (size_t)h->nb * 64 * 4});
+            p.push_back({reinterpret_cast<void **>(&pd.nmeta), (size_t)h->nb * 64});
+            p.push_back({&pd.nsw, (size_t)(h->nb * h->slots) * h->narrow_sw_bytes});
+            continue;
+        }
         p.push_back({reinterpret_cast<void **>(&pd.entries), (size_t)(h->nb * pd.S * rsr::kSlab) * 2});
         p.push_back({reinterpret_cast<void **>(&pd.start), (size_t)(h->nb * h->W * 64) * 2});
         p.push_back({&pd.sgn, sign_table_bytes(h)});
@@ -581,7 +622,7 @@ std::vector<Piece> pieces_of(rsr_handle_s *h) {
             p.push_back({reinterpret_cast<void **>(&pd.gcount), (size_t)h->nb * 4});
         }
     }
-    if (!h->by_rank) {
+    if (!h->by_rank && !h->narrow) {
         p.push_back({reinterpret_cast<void **>(&h->fpack), (size_t)h->k * h->fold.G * 64 * 4});
         p.push_back({reinterpret_cast<void **>(&h->fshare), (size_t)h->W * 64 * 4});
     }
@@ -610,7 +651,7 @@ int rsr_serialize(rsr_handle_t h, void *host_buf, int64_t capacity) {
     hd.magic = kSerialMagic;
     hd.version = kSerialVersion;
     hd.kind = h->kind; hd.k = h->k; hd.base = h->base; hd.npass = h->npass;
-    hd.W = h->W; hd.by_rank = h->by_rank; hd.enc = h->enc; hd.slots = h->slots;
+    hd.W = h->W; hd.by_rank = h->by_rank; hd.enc = h->enc; hd.slots = h->slots; hd.narrow = h->narrow;
     hd.rows = h->rows; hd.cols = h->cols; hd.nb = h->nb; hd.P = h->P; hd.row_bytes = h->row_bytes;
     for (int ps = 0; ps < 2; ++ps) { hd.S[ps] = h->pass[ps].S; hd.sign[ps] = h->pass[ps].sign; }
     hd.total_bytes = total;
@@ -646,13 +687,17 @@ rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size) {
     } else if (ok) {
         const bool fused = hd.kind == RSR_TERNARY_FUSED;
         ok = hd.k >= 1 && hd.k <= (fused ? 10 : 15) && hd.base == (fused ? 3 : 2) &&
-             hd.npass == (hd.kind == RSR_TERNARY_2PASS ? 2 : 1) && hd.W >= 1 && hd.W <= rsr::kMaxWaves &&
-             (hd.by_rank == 0 || hd.by_rank == 1) &&
-             hd.enc == (hd.cols <= rsr::kSmallCols ? rsr::kEncSmall : rsr::kEncBig);
-        if (ok) {
-            // slots: P by code; by rank at most one per column (every slot owns a tail entry),
-            // and the kernel addresses LDS with it, so it has to fit
-            ok = hd.P == ipow(hd.base, hd.k) && hd.nb == (hd.rows + hd.k - 1) / hd.k &&
+             hd.npass == (hd.kind == RSR_TERNARY_2PASS ? 2 : 1) && (hd.narrow == 0 || hd.narrow == 1) &&
+             hd.P == ipow(hd.base, hd.k) && hd.nb == (hd.rows + hd.k - 1) / hd.k;
+        if (ok && hd.narrow) {
+            // at most one group per column; the kernel reads sign words 4 at a time
+            ok = hd.cols <= rsr::kNarrowCols && hd.k * (fused ? 2 : 1) <= 32 && hd.slots >= 4 &&
+                 hd.slots <= 256 && hd.slots % 4 == 0;
+        } else if (ok) {
+            ok = hd.W >= 1 && hd.W <= rsr::kMaxWaves && (hd.by_rank == 0 || hd.by_rank == 1) &&
+                 hd.enc == (hd.cols <= rsr::kSmallCols ? rsr::kEncSmall : rsr::kEncBig) &&
+                 // slots: P by code; by rank at most one per column (every slot owns a tail
+                 // entry), and the kernel addresses LDS with it, so it has to fit
                  (hd.by_rank ? (hd.slots >= 1 && hd.slots <= hd.cols + 1) : hd.slots == hd.P) &&
                  rsr::matvec_lds_bytes(hd.slots, hd.cols, 4, hd.W, hd.by_rank != 0) <= rsr::kLdsBytes;
             for (int ps = 0; ok && ps < hd.npass; ++ps)
@@ -665,10 +710,14 @@ rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size) {
     if (!h) { fail(RSR_ENOMEM); return nullptr; }
     h->magic = rsr::kMagic;
     h->kind = hd.kind; h->k = hd.k; h->base = hd.base; h->npass = hd.npass;
-    h->W = hd.W; h->by_rank = hd.by_rank; h->enc = hd.enc; h->slots = hd.slots;
+    h->W = hd.W; h->by_rank = hd.by_rank; h->enc = hd.enc; h->slots = hd.slots; h->narrow = hd.narrow;
+    if (h->narrow) {
+        h->narrow_fw = h->base == 2 ? 1 : 2;
+        h->narrow_sw_bytes = h->k * h->narrow_fw <= 8 ? 1 : h->k * h->narrow_fw <= 16 ? 2 : 4;
+    }
     h->rows = hd.rows; h->cols = hd.cols; h->nb = hd.nb; h->P = hd.P; h->row_bytes = hd.row_bytes;
     for (int ps = 0; ps < 2; ++ps) { h->pass[ps].S = hd.S[ps]; h->pass[ps].sign = hd.sign[ps]; }
-    if (!dense && !h->by_rank) rsr::make_fold_shape(h->base, h->k, h->P, h->W, &h->fold);
+    if (!dense && !h->by_rank && !h->narrow) rsr::make_fold_shape(h->base, h->k, h->P, h->W, &h->fold);
     int rc = RSR_OK;
     if (hipGetDevice(&h->device) != hipSuccess) rc = RSR_EHIP;
     const std::vector<Piece> pieces = pieces_of(h);
@@ -708,6 +757,9 @@ int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void 
     hipError_t e = (h->kind == RSR_DENSE_TERNARY_P2)
                        ? rsr::launch_dense_matvec(h, v, v_dtype, scale, static_cast<float *>(out),
                                                   batch, ldv, ldo, s)
+                   : h->narrow
+                       ? rsr::launch_narrow_matvec(h, v, v_dtype, scale, static_cast<float *>(out), batch, ldv,
+                                                   ldo, s)
                        : rsr::launch_rsr_matvec(h, v, v_dtype, scale, static_cast<float *>(out),
                                                 batch, ldv, ldo, s);
     if (e != hipSuccess) return fail(hip_code(e));
@@ -734,6 +786,7 @@ int rsr_probe_read(const void *src, int64_t bytes, int workgroups, int threads, 
 int rsr_launch_shape(rsr_handle_t h, int v_dtype, int *workgroups, int *threads, int *lds_bytes) {
     if (!good(h) || !is_rsr_kind(h->kind) || (v_dtype != RSR_F32 && v_dtype != RSR_BF16))
         return fail(RSR_EINVAL);
+    if (h->narrow) return fail(RSR_EUNSUPPORTED);
     if (workgroups) *workgroups = (int)h->nb;
     if (threads) *threads = h->W * 64;
     if (lds_bytes)
@@ -830,11 +883,13 @@ int64_t rsr_algorithmic_bytes(rsr_handle_t h, int v_dtype, int batch) {
         weight_side = (h->rows + rsr::kDenseRows - 1) / rsr::kDenseRows * rsr::kDenseRows * h->row_bytes;
     } else {
         weight_side = 0;
-        for (int ps = 0; ps < h->npass; ++ps)
+        for (int ps = 0; h->narrow && ps < h->npass; ++ps)
+            weight_side += h->nb * (64 * 4 + 64 + h->slots * h->narrow_sw_bytes);
+        for (int ps = 0; !h->narrow && ps < h->npass; ++ps)
             weight_side += h->nb * (h->pass[ps].S * (int64_t)rsr::kSlab * 2 + (int64_t)h->W * 64 * 2 +
                                     (h->by_rank ? h->slots * 4 + 4 : 0)) +
                            (int64_t)sign_table_bytes(h);
-        if (!h->by_rank) weight_side += (int64_t)h->k * h->fold.G * 256 + (int64_t)h->W * 64 * 4;
+        if (!h->by_rank && !h->narrow) weight_side += (int64_t)h->k * h->fold.G * 256 + (int64_t)h->W * 64 * 4;
     }
     return weight_side + (int64_t)batch * (h->cols * vb + h->rows * 4);
 }
@@ -845,6 +900,7 @@ const char *rsr_kernel_name(rsr_handle_t h, int v_dtype) {
         return nullptr;
     }
     if (h->kind == RSR_DENSE_TERNARY_P2) return rsr::dense_matvec_kernel_name(h, v_dtype);
+    if (h->narrow) return v_dtype == RSR_BF16 ? "k_rsr_narrow<unsigned short>" : "k_rsr_narrow<float>";
     static thread_local char name[96];
     rsr::rsr_matvec_kernel_name(h, v_dtype, name, sizeof(name));
     return name;

@@ -58,6 +58,11 @@ struct PassData {
     //            when W <= 8, else 32-bit)
     //   by rank: [nb][W][64] 32-bit words, (w, l) holds the k rows at bits 2r
     void *sgn = nullptr;
+    // narrow handles (cols <= 256, see rsr_narrow.hip): entries of a block four per lane, one
+    // byte each; tail and valid flags per lane; sign words of the groups in rank order
+    uint32_t *nent = nullptr;     // [nb][64]
+    uint8_t *nmeta = nullptr;     // [nb][64]
+    void *nsw = nullptr;          // [nb][slots], narrow_sw_bytes each
     uint32_t *gword = nullptr;    // by rank: [nb][slots] difference weights of every slot, fw bits per row
     uint32_t *gcount = nullptr;   // by rank: [nb] non-empty groups of the block
     int64_t S = 0;                // slabs per block
@@ -80,6 +85,8 @@ struct rsr_handle_s {
     int kind = 0, k = 0, base = 0, npass = 0, device = 0;
     int W = 0;        // waves per workgroup of the multiply kernel
     int enc = 0;      // entry encoding: kEncSmall or kEncBig
+    int narrow = 0;   // cols <= 256: one wave per block, 8-bit entries (slots = sign words per block)
+    int narrow_fw = 0, narrow_sw_bytes = 0;  // bits per row in a sign word, bytes per sign word
     int by_rank = 0;  // E indexed by group rank (no placeholders) instead of by pattern code
     int64_t rows = 0, cols = 0, nb = 0, P = 0;
     int64_t slots = 0;  // entries of E: P (by code) or 1 + the most non-empty groups of a block
@@ -138,6 +145,12 @@ hipError_t launch_dense_matvec(const rsr_handle_s *h, const void *v, int v_dtype
 // Writes the name of the multiply kernel h launches for (v_dtype, batch) into buf.
 void rsr_matvec_kernel_name(const rsr_handle_s *h, int v_dtype, char *buf, size_t len);
 const char *dense_matvec_kernel_name(const rsr_handle_s *h, int v_dtype);
+
+// --- narrow matrices (cols <= kNarrowCols) ---------------------------------------------
+constexpr int kNarrowCols = 256;
+hipError_t launch_pack_narrow(const rsr_handle_s *h, int pass, int *err_flag);
+hipError_t launch_narrow_matvec(const rsr_handle_s *h, const void *v, int v_dtype, float scale, float *out,
+                                int batch, int64_t ldv, int64_t ldo, hipStream_t stream);
 
 // --- reference launches of the benchmark ---------------------------------------------
 hipError_t launch_probe_empty(int workgroups, int threads, int lds_bytes, hipStream_t stream);

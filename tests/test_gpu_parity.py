@@ -96,6 +96,15 @@ CASES = [
     (rsr.RSR_BINARY, 30, 3000, 14),
     (rsr.RSR_TERNARY_2PASS, 20, 2048, 15),
     (rsr.RSR_TERNARY_2PASS, 45, 30000, 11),
+    # at most 256 columns: one wave per block, 8-bit entries
+    (rsr.RSR_BINARY, 300, 256, 8),
+    (rsr.RSR_BINARY, 1000, 255, 4),
+    (rsr.RSR_BINARY, 40, 100, 15),
+    (rsr.RSR_BINARY, 50, 1, 3),
+    (rsr.RSR_TERNARY_FUSED, 100, 256, 5),
+    (rsr.RSR_TERNARY_FUSED, 33, 255, 8),
+    (rsr.RSR_TERNARY_FUSED, 45, 100, 10),
+    (rsr.RSR_TERNARY_2PASS, 64, 129, 8),
 ]
 
 
@@ -187,9 +196,15 @@ def test_batch_and_strides():
     (rsr.RSR_TERNARY_2PASS, True, 8, 5), (rsr.RSR_DENSE_TERNARY_P2, True, 0, 5),
     (rsr.RSR_DENSE_TERNARY_P2, True, 5, 19), (rsr.RSR_DENSE_TERNARY_P2, False, 2, 6)])
 def test_batch_many_blocks(kind, bf16, pad, batch):
-    """Enough blocks that one workgroup takes several vectors in turn; aligned and
-    unaligned vector strides; integer-valued vectors, so every output is exact."""
-    rows, cols, k = 2100, 264, 2
+    """Many blocks and several vectors in one call; aligned and unaligned vector strides;
+    integer-valued vectors, so every output is exact.  264 columns take the general kernel,
+    200 columns the one for narrow matrices."""
+    for cols in (264, 200):
+        _batch_many_blocks(kind, bf16, pad, batch, cols)
+
+
+def _batch_many_blocks(kind, bf16, pad, batch, cols):
+    rows, k = 2100, 2
     M = _matrix(kind, rows, cols, 77)
     h = rsr.rsr_preprocess(_dev(M), k, kind)
     vi = np.stack([gen.integer_f32(cols, seed=900 + i) for i in range(batch)])

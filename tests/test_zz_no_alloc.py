@@ -84,9 +84,9 @@ def test_refusals_leave_the_library_usable():
     assert torch.equal(rsr.rsr_matvec(h, v), before)
     rsr.rsr_destroy(h)
     # temporaries beyond the fixed scratch array: refused before anything is written
-    rows, cols = 200000, 256
+    rows, cols = 30000, 2048
     big = gen.binary_matrix(rows, cols, 0.3, 7)
-    hb = rsr.rsr_preprocess(_dev(big), 8, rsr.RSR_BINARY)
+    hb = rsr.rsr_preprocess(_dev(big), 4, rsr.RSR_BINARY)
     vb = _dev(gen.integer_f32(cols, seed=8))
     before = rsr.rsr_matvec(hb, vb).clone()
     with pytest.raises(rsr.RsrError) as e:
