@@ -155,6 +155,11 @@ def time_stream(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS):
         return [marks[r].elapsed_time(marks[r + 1]) for r in range(replays)]
 
 
+def log(msg):
+    """Progress line on stderr (the JSON line on stdout stays the only output there)."""
+    print("bench.py: " + msg, file=sys.stderr, flush=True)
+
+
 def median(xs):
     xs = sorted(xs)
     n = len(xs)
@@ -350,6 +355,7 @@ def main():
 
     # two ways of issuing the same K launches; short replays are timed with plain launches (a
     # graph replay carries a fixed begin/end cost of about 12 us that would be spread over K)
+    log("%d weight sets preprocessed; timing" % nsets)
     times_graph = time_graphs(torch, cold, args.steps, args.warmup, period=nsets)
     times_plain = (time_stream(torch, cold, args.steps, args.warmup, period=nsets)
                    if args.steps <= PLAIN_LAUNCH_MAX_STEPS else None)
@@ -419,6 +425,7 @@ def main():
     if not args.no_extras:
         # the reference legs, same protocol and launch geometry: a launch that does nothing, and
         # a launch that only reads the same number of bytes once
+        log("headline %.3f us/step; reference legs" % us_per_step)
         wg, th, lds = rsr.rsr_launch_shape(h0, rsr.RSR_BF16)
         read_bytes = alg_bytes // 1024 * 1024
         pool = torch.randint(0, 255, (nsets * read_bytes,), dtype=torch.uint8, device=dev)
@@ -437,11 +444,13 @@ def main():
                     "discards them, each in the multiply kernel's launch geometry: what one launch per "
                     "product costs on this protocol before any arithmetic",
         }
+        log("warm leg")
         ms_w = timed(warm)
         result["warm"] = {"matvec_per_s": args.steps / (ms_w * 1e-3),
                           "us_per_step": ms_w * 1e3 / args.steps,
                           "note": "single weight set, Infinity-Cache resident: not an HBM figure"}
         # dense packed-2-bit comparison kernel, same protocol
+        log("dense comparison kernel")
         dsets = int(np.ceil(COLD_WORKING_SET / dense_equiv_bytes))
         for hh in handles[1:]:
             rsr.rsr_destroy(hh)
@@ -484,6 +493,7 @@ def main():
         # one thread, then the same routine on row slices from one thread per core (the C call
         # releases the interpreter lock), about 10 s each; and the oracle's own RSR multiply
         from concurrent.futures import ThreadPoolExecutor
+        log("oracle on the host cores")
         v64 = vals.astype(np.float64)
         t0 = time.time()
         n1 = 0
