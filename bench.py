@@ -284,7 +284,7 @@ def run_configs(args):
             one("8B layers (3)", layers_8b, k, TF, True, batch=batch, max_sets=12)
         one("8B layers (3)", layers_8b, 0, D, True, batch=batch, max_sets=12)
     table = lambda i: [gen.column_density_binary(1 << 20, 256, 0.05, 0.5, s0 + 900 + i)]
-    for k in (4, 8):
+    for k in (4, 8, 12, 0):
         one("retrieval 1048576x256", table, k, B, False, max_sets=6)
     one("retrieval 1048576x256", table, 0, D, False, max_sets=6)
     # 64 queries: back to back (the timed loop above is exactly that, per query) or one call

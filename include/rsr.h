@@ -74,7 +74,10 @@ enum {
  * significant first; binary digits {0,1} base 2; fused digits 0,1,2 for
  * 0,+1,-1 base 3.  The handle keeps, per pass, the canonical artifacts
  * (column permutation pi, group boundaries off; see the getters) and the
- * compact stream the multiply kernel reads.
+ * compact stream the multiply kernel reads: 16-bit column entries with one tail flag per
+ * group (8-bit entries, tail bits and one sign word per existing group when cols <= 256);
+ * the per-group prefix array of the kernel is indexed by pattern code, or by the rank of the
+ * group among the existing ones when P is much larger than cols.
  *
  * Runs on the current HIP device, on the null stream, and synchronises
  * before returning.  Returns NULL on failure (see rsr_last_error()).
@@ -107,6 +110,11 @@ int rsr_matvec(rsr_handle_t h, const void *v, void *out, void *stream);
  *   scale   per-tensor scale applied to every output
  *   batch   number of vectors (>= 1); vector i starts at v + i*ldv elements,
  *           its result at out + i*ldo elements (ldv >= cols, ldo >= rows)
+ *
+ * A batch is one launch.  The dense kind multiplies up to 16 vectors per pass over the
+ * weights.  The RSR kinds give every vector its own workgroups (the weight side is then
+ * read from HBM once and from the caches by the other vectors).  The result of a vector
+ * does not depend on the batch it is part of (bit for bit).
  */
 int rsr_matvec_ex(rsr_handle_t h, const void *v, int v_dtype, float scale, void *out,
                   int batch, int64_t ldv, int64_t ldo, void *stream);
@@ -178,8 +186,11 @@ rsr_handle_t rsr_deserialize(const void *host_buf, int64_t size);
  *   M  DEVICE int8 [rows][cols] with the handle's rows and cols; borrowed
  *
  * Temporary memory needed: 256 bytes for the dense kind; otherwise, each term rounded
- * up to 256 bytes, 256 + 4*nb + 2*nb*cols + 2*nb*S with nb = ceil(rows/k) and S the
- * stream slots per block of the handle (at most cols + P rounded up to 2048).  More than
+ * up to 256 bytes, 256 + 2*nb*cols (pattern codes) + 1024*nb*S (the stream in logical
+ * order; not for matrices of at most 256 columns, whose layout is written directly)
+ * + 2*nb*slots (group codes; only for handles whose prefix array is indexed by group rank),
+ * with nb = ceil(rows/k), S the 512-entry slabs per block and slots the prefix-array
+ * length of the handle.  More than
  * RSR_INTO_SCRATCH_BYTES: RSR_ESCRATCH, handle untouched.  A matrix whose stream needs
  * more slots per block than the handle holds (more empty pattern groups than the matrix
  * the handle was made from): RSR_EUNSUPPORTED; an entry outside the alphabet: RSR_EVALUE.
@@ -250,7 +261,8 @@ int rsr_probe_read(const void *src, int64_t bytes, int workgroups, int threads, 
 
 /*
  * Name of the multiply kernel this handle launches for a vector type (the
- * symbol a profiler reports), or NULL on a bad argument.  Static storage.
+ * symbol a profiler reports; the same for every batch size), or NULL on a bad
+ * argument.  Static storage (per thread; the next call overwrites it).
  */
 const char *rsr_kernel_name(rsr_handle_t h, int v_dtype);
 

@@ -7,6 +7,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import warnings
 from typing import Optional
 
 import numpy as np
@@ -45,6 +46,11 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     path = path or _build.LIB_PATH
     if not os.path.exists(path):
         _build.build_library()
+    elif path == _build.LIB_PATH:
+        newer = _build.sources_newer_than_library()
+        if newer:
+            warnings.warn("librsr.so is older than %s: it does not contain the current sources; "
+                          "rebuild with paper_2603_27462_amd.build.build_library()" % ", ".join(newer))
     # PyTorch ships its own HIP runtime; it has to be in the process first so that
     # librsr binds to the same one the tensors were allocated with.
     import torch  # noqa: F401

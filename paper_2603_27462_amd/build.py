@@ -38,5 +38,16 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def sources_newer_than_library() -> list:
+    """Source files modified after the built library (empty when it is up to date or absent)."""
+    if not os.path.exists(LIB_PATH):
+        return []
+    built = os.path.getmtime(LIB_PATH)
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC))]
+    files.append(os.path.join(INCLUDE, "rsr.h"))
+    return [os.path.relpath(f, os.path.dirname(PKG_DIR)) for f in files
+            if f.endswith((".hip", ".h")) and os.path.getmtime(f) > built + 1.0]
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))

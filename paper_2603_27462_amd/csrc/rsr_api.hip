@@ -212,7 +212,7 @@ int preprocess_rsr(rsr_handle_s *h, const int8_t *M, bool allow_narrow) {
             if (st.groups[ps] > most) most = st.groups[ps];
         }
         h->slots = h->by_rank ? most + 1 : P;
-        h->W = rsr::choose_waves(maxS, nb);
+        h->W = rsr::choose_waves(maxS, nb, h->k, h->by_rank != 0);
         h->enc = (cols <= rsr::kSmallCols) ? rsr::kEncSmall : rsr::kEncBig;
         if (rsr::matvec_lds_bytes(h->slots, cols, 4, h->W, h->by_rank != 0) > rsr::kLdsBytes) {
             rc = RSR_EUNSUPPORTED;

@@ -157,8 +157,8 @@ hipError_t launch_probe_empty(int workgroups, int threads, int lds_bytes, hipStr
 hipError_t launch_probe_read(const void *src, int64_t bytes, int workgroups, int threads, void *sink,
                              hipStream_t stream);
 
-// Waves per workgroup for nb blocks whose longest stream has `slabs` slabs.
-int choose_waves(int64_t slabs, int64_t nb);
+// Waves per workgroup for nb blocks of k rows whose longest stream has `slabs` slabs.
+int choose_waves(int64_t slabs, int64_t nb, int k, bool by_rank);
 // True when E is better indexed by group rank: P floats do not fit LDS, or the placeholders
 // of a code-indexed stream would outweigh the per-group weight words.
 bool choose_by_rank(int64_t P, int64_t cols, int64_t longest_by_code, int64_t longest_by_rank,

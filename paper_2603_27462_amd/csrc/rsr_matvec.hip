@@ -648,19 +648,34 @@ __global__ void k_fold_tables(int k, FoldShape fs, int threads, uint32_t *__rest
 
 }  // namespace
 
-int choose_waves(int64_t slabs, int64_t nb) {
-    // Preferred: at most four slabs per wave (one group, every load requested up front) and
-    // at most 8 waves, so that two workgroups share a CU without register pressure; a wave
-    // takes 1, 2 or 4 slabs as the stream grows.  Longer streams take up to 16 waves, and
-    // beyond that 8 waves that work through several groups.
-    // A CU runs 16 of these waves: with three or more rounds of 8-wave workgroups (1536
-    // blocks) it pays to halve the waves per block and keep twice as many blocks in flight.
-    const int cap = nb >= 1536 ? 4 : 8;
-    int per = kGroupSlabs;
-    for (int cand = 1; cand <= kGroupSlabs; cand *= 2)
-        if ((slabs + cand - 1) / cand <= cap) { per = cand; break; }
-    const int64_t waves = (slabs + per - 1) / per;
-    int w = (int)(waves < 1 ? 1 : waves <= kMaxWaves ? waves : 8);
+int choose_waves(int64_t slabs, int64_t nb, int k, bool by_rank) {
+    // A wave should own at most four slabs (one group: every load of the wave is requested
+    // up front).
+    const int64_t need = (slabs + kGroupSlabs - 1) / kGroupSlabs;
+    int w;
+    if (!by_rank && k <= 8) {
+        // E by code, up to eight rows: one wave per output row.  The second level of the
+        // scatter phase then is one straight pass per wave; fewer waves make some of them
+        // loop over rows (measured 15 to 30 % slower), more waves only add the fixed cost a
+        // wave has (4096 x 4096: fused k = 4, 6, 8 best at 4, 6, 8 waves; binary 1024 x 1024,
+        // k = 8, three slabs: 4.5 us with three waves, 3.4 us with eight, five of them
+        // without a slab).  Longer streams take more waves, beyond 16 eight waves that work
+        // through several groups.
+        w = (int)(need > k ? need : k);
+        if (w > kMaxWaves) w = 8;
+    } else {
+        // Otherwise 1, 2 or 4 slabs per wave as the stream grows and at most 8 waves, so that
+        // two workgroups share a CU; with three or more rounds of 8-wave workgroups (1536
+        // blocks) half the waves per block keep twice as many blocks in flight.  E by code
+        // with more than eight rows: at most two rows per wave.
+        const int cap = nb >= 1536 ? 4 : 8;
+        int per = kGroupSlabs;
+        for (int cand = 1; cand <= kGroupSlabs; cand *= 2)
+            if ((slabs + cand - 1) / cand <= cap) { per = cand; break; }
+        const int64_t waves = (slabs + per - 1) / per;
+        w = (int)(waves < 1 ? 1 : waves <= kMaxWaves ? waves : 8);
+        if (!by_rank && w < 8 && 2 * w < k) w = (k + 1) / 2 < 8 ? (k + 1) / 2 : 8;
+    }
 #ifdef RSR_TUNING
     if (const char *s = std::getenv("RSR_W")) {
         const int x = std::atoi(s);

@@ -219,6 +219,36 @@ def _batch_many_blocks(kind, bf16, pad, batch, cols):
         assert np.array_equal(got[i, :rows].astype(np.float64), want), "vector %d" % i
 
 
+@pytest.mark.parametrize("kind,rows,cols,k,batch,bf16,pad", [
+    (rsr.RSR_TERNARY_FUSED, 2600, 300, 10, 3, True, 0),     # E by rank
+    (rsr.RSR_TERNARY_2PASS, 2600, 1500, 5, 4, False, 1),    # two passes per vector, unaligned vectors
+    (rsr.RSR_BINARY, 1024, 1024, 8, 7, False, 0),           # 128 blocks, five of eight waves without a slab
+    (rsr.RSR_BINARY, 3120, 30000, 12, 3, True, 0),          # several groups of slabs per wave
+    (rsr.RSR_TERNARY_FUSED, 4096, 1000, 8, 4, True, 4),     # the common class count, short stream
+    (rsr.RSR_BINARY, 3100, 2000, 2, 5, True, 0)])           # four waves per block
+def test_batch_shapes(kind, rows, cols, k, batch, bf16, pad):
+    """Batches over the launch shapes of the multiply kernel: integer-valued vectors, so
+    every output of every vector is exact; rows past the matrix stay untouched."""
+    if cols >= 30000:
+        M = gen.dictionary_binary_matrix(rows, cols, k, 1000, 5)   # 30000 entries + 3100 placeholders
+    else:
+        M = _matrix(kind, rows, cols, 78)
+    h = rsr.rsr_preprocess(_dev(M), k, kind)
+    vi = np.stack([gen.integer_f32(cols, seed=300 + i) for i in range(batch)])
+    vbuf = torch.zeros((batch, cols + pad), dtype=torch.bfloat16 if bf16 else torch.float32, device=DEV)
+    vbuf[:, :cols] = _dev(vi).to(vbuf.dtype)
+    out = torch.full((batch, rows + 5), -7.0, dtype=torch.float32, device=DEV)
+    rsr.rsr_matvec_ex(h, vbuf[:, :cols], scale=-2.0, out=out[:, :rows])
+    got = out.cpu().numpy()
+    assert np.all(got[:, rows:] == -7.0)
+    for i in range(batch):
+        want = oracle.dense_matvec(M, vi[i].astype(np.float64), -2.0)
+        assert np.array_equal(got[i, :rows].astype(np.float64), want), "vector %d" % i
+    # and one vector alone gives the same bits as it did inside the batch
+    alone = rsr.rsr_matvec_ex(h, vbuf[1, :cols], scale=-2.0).cpu().numpy()
+    assert np.array_equal(alone, got[1, :rows])
+
+
 @pytest.mark.parametrize("kind,k", [(rsr.RSR_TERNARY_FUSED, 6), (rsr.RSR_TERNARY_2PASS, 5),
                                     (rsr.RSR_BINARY, 8), (rsr.RSR_DENSE_TERNARY_P2, 0)])
 def test_serialize_round_trip(kind, k):
