@@ -107,7 +107,8 @@ __device__ __forceinline__ void pin(T &x) {
 // (the entries that agree with t in the m lowest digits) and leaves the sum in
 // C1[part][t]; a class is shared by at most two threads.  Every thread adds the same
 // number of entries (cnt1): E is followed by one row of Tc zeros, which the second part
-// reads when Q is odd.
+// reads when Q is odd.  With Q == 1 (all P codes fit the workgroup) the class sums are E
+// itself and level 1 and its barrier are left out.
 // Level 2: one wave per output row.  Rows r < m weigh the class sums with the weight of
 // (t, r); rows r >= m weigh E[Tc i + Tc - 1], the only entries where their digit
 // changes, with the weight of (i, r).  Lane l adds the totals of the strips (w, l), each
@@ -155,7 +156,8 @@ __device__ __forceinline__ void prepare_scatter(ScatterPrep &sp, const FoldArgs 
     const int r = min(w, f.k - 1);
     const bool low = r < f.m;
     const int n = low ? Tc : f.Q;
-    const uint32_t base = low ? c1_at : e_at + (uint32_t)(Tc - 1) * 4u;
+    // with one entry per class (Q == 1) the class sums are E itself: no level 1
+    const uint32_t base = low ? (f.Q == 1 ? e_at : c1_at) : e_at + (uint32_t)(Tc - 1) * 4u;
     const uint32_t stride = low ? 4u : step;
     const uint32_t last = base + stride * (uint32_t)(n - 1);
     sp.la[0] = min(base + stride * (uint32_t)lane, last);
@@ -210,7 +212,7 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
                                                 uint32_t c1_at, int W, int w, int lane,
                                                 float sign_scale, float *out_rows,
                                                 long long rows_left) {
-    if (sp.has_share) {
+    if (f.Q > 1 && sp.has_share) {
         // the thread's cnt1 entries, E[first + i Tc]: whole batches of four, then the rest one
         // by one (wave-uniform branches; the loads of a batch are in flight together)
         const uint32_t step = class_step<TC>(f);
@@ -252,7 +254,7 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
         const float col = x[0] + rest;
         *lds_float(sp.c1_store) = col;
     }
-    __syncthreads();
+    if (f.Q > 1) __syncthreads();
     if (f.G == 1 && f.k <= W) {
         // common shape: at most one row per wave, at most 256 table entries per row
         if (w < f.k) {
@@ -283,7 +285,7 @@ __device__ __forceinline__ void scatter_by_code(const FoldArgs &f, const Scatter
         const bool low = r < f.m;
         const int n = low ? f.Tc : f.Q;
         // element j of the row: class sum C1[0][j] (+ C1[1][j]), or E[Tc j + Tc - 1]
-        const uint32_t base = low ? c1_at : e_at + (uint32_t)(f.Tc - 1) * 4u;
+        const uint32_t base = low ? (f.Q == 1 ? e_at : c1_at) : e_at + (uint32_t)(f.Tc - 1) * 4u;
         const uint32_t stride = low ? 4u : class_step<TC>(f);
         const bool two = low && f.parts == 2;
         const uint32_t second = class_step<TC>(f);
