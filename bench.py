@@ -63,7 +63,7 @@ MIN_REPLAYS = 11              # timed replays (the median is reported)
 PLAIN_LAUNCH_MAX_STEPS = 512  # up to here the K launches are also timed without a graph
 
 
-def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS):
+def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS, lanes=1):
     """Times `steps` back-to-back launches, captured in HIP graphs, between two HIP events
     on the launch stream; returns the per-replay times in ms (one replay = exactly `steps`
     launches).
@@ -74,9 +74,13 @@ def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS):
     covers launches r*steps .. r*steps + steps - 1, one captured graph per distinct window,
     so the distance between two uses of the same weight set is `period` launches whatever
     `steps` is.
+
+    lanes = 2 deals the launches of a graph alternately to two streams (two independent
+    chains in the captured graph): consecutive launches may then overlap on the GPU.
     """
     from math import gcd
     stream = torch.cuda.Stream()
+    side = torch.cuda.Stream() if lanes == 2 else None
     # (long replays visit every weight set many times: one graph serves)
     ngraphs = period // gcd(steps % period, period) if (steps % period and steps < 8 * period) else 1
     with torch.cuda.stream(stream):
@@ -87,8 +91,12 @@ def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS):
         for gi in range(ngraphs):
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
+                if side is not None:
+                    side.wait_stream(stream)
                 for i in range(steps):
-                    launch_fn(gi * steps + i, stream)
+                    launch_fn(gi * steps + i, side if (side is not None and i % 2) else stream)
+                if side is not None:
+                    stream.wait_stream(side)
             graphs.append(graph)
         # untimed warm-up launches through the same path: every graph once, at least `warmup` launches
         reps = max(ngraphs, (warmup + steps - 1) // steps)
@@ -449,6 +457,13 @@ def main():
         result["warm"] = {"matvec_per_s": args.steps / (ms_w * 1e-3),
                           "us_per_step": ms_w * 1e3 / args.steps,
                           "note": "single weight set, Infinity-Cache resident: not an HBM figure"}
+        # what independent products gain when two launch chains may overlap (not the metric:
+        # a batch-1 decode is one dependent chain)
+        two = None
+        if args.steps >= 8 * nsets:
+            log("two launch chains")
+            ms_2 = median(time_graphs(torch, cold, args.steps, args.warmup, nsets, lanes=2))
+            two = {"rsr_us_per_step": ms_2 * 1e3 / args.steps}
         # dense packed-2-bit comparison kernel, same protocol
         log("dense comparison kernel")
         dsets = int(np.ceil(COLD_WORKING_SET / dense_equiv_bytes))
@@ -487,6 +502,13 @@ def main():
             "frac_mfma_bf16_peak": rows * cols * 16 * 2 / (ms_d * 1e-3 / args.steps) / 2.5e15,
         }
         result["speedup_vs_dense_packed2"] = ms_d / ms
+        if two is not None:
+            two["dense_us_per_step"] = median(time_graphs(torch, dcold, args.steps, args.warmup, dsets,
+                                                          lanes=2)) * 1e3 / args.steps
+            two["note"] = ("the same cold launches dealt alternately to two streams of one graph, so that "
+                           "the start-up of one launch overlaps the end of the other: throughput of "
+                           "independent products, reported beside the metric and not part of it")
+            result["two_launch_chains"] = two
 
     if not args.no_cpu_baseline:
         # the oracle as it stands (plain C, float64), on the host cores: the dense definition on
