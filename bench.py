@@ -47,6 +47,9 @@ def parse_args():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="also run one plain device copy of 256 MiB (a kernel of known traffic, "
                          "to calibrate rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--no-two-chains", action="store_true",
+                    help="skip the leg in which two launch chains overlap (its kernels run "
+                         "concurrently, which blurs a per-kernel trace)")
     ap.add_argument("--max-sets", type=int, default=40, help="with --configs: weight sets per workload at most")
     ap.add_argument("--no-auto-k", action="store_true", help="with --configs: skip the lines where the "
                                                              "library chooses k (many extra launches)")
@@ -460,7 +463,7 @@ def main():
         # what independent products gain when two launch chains may overlap (not the metric:
         # a batch-1 decode is one dependent chain)
         two = None
-        if args.steps >= 8 * nsets:
+        if args.steps >= 8 * nsets and not args.no_two_chains:
             log("two launch chains")
             ms_2 = median(time_graphs(torch, cold, args.steps, args.warmup, nsets, lanes=2))
             two = {"rsr_us_per_step": ms_2 * 1e3 / args.steps}
