@@ -7,9 +7,13 @@ ternary 4096 x 14336 matrix (P(0)=0.35, P(+1)=P(-1)=0.325), one bf16 vector,
 float32 output.  Preprocessing is done once before the timed region; all
 handles, vectors and outputs are resident in HBM when timing starts.
 
-Timed region: K launches back to back on one stream inside one HIP graph,
-bracketed by HIP events on that stream; at least eleven such replays are
-timed and the median is reported.  Launch i uses weight set i mod H, with H
+One replay is K launches back to back on one stream (one HIP graph; for short
+replays plain launches queued behind a spin kernel are timed as well and the
+faster way counts).  A timed region is bracketed by HIP events on that stream
+and holds as many consecutive replays as make at least 1000 launches (one
+replay when K >= 1000), its time divided by their number: the per-replay time
+does not carry the two event records.  At least eleven regions are timed and
+the median is reported.  Launch i uses weight set i mod H, with H
 distinct preprocessed matrices whose streams together exceed twice the 256 MB
 Infinity Cache, and consecutive replays continue the rotation, so every launch
 streams its weights from HBM ("cold") whatever K is.  Extra fields: the same
@@ -66,7 +70,7 @@ MIN_REPLAYS = 11              # timed replays (the median is reported)
 PLAIN_LAUNCH_MAX_STEPS = 512  # up to here the K launches are also timed without a graph
 
 
-def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS, lanes=1):
+def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS, lanes=1, chain=1):
     """Times `steps` back-to-back launches, captured in HIP graphs, between two HIP events
     on the launch stream; returns the per-replay times in ms (one replay = exactly `steps`
     launches).
@@ -80,6 +84,10 @@ def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS, 
 
     lanes = 2 deals the launches of a graph alternately to two streams (two independent
     chains in the captured graph): consecutive launches may then overlap on the GPU.
+
+    chain > 1: a timed region holds `chain` consecutive replays (chain * steps launches) and
+    its time is divided by `chain`: with few steps per replay the two event records around a
+    region would otherwise weigh as much as a launch.
     """
     from math import gcd
     stream = torch.cuda.Stream()
@@ -110,17 +118,20 @@ def time_graphs(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS, 
         # the timed replays are enqueued back to back with an event between each two, and the
         # host waits once at the end: the GPU never idles between replays (idle gaps let its
         # clocks drop), and every interval between two events holds exactly `steps` launches
-        nrep = max(replays, ngraphs)
+        nrep = max(replays, -(-ngraphs // chain))
         if steps <= PLAIN_LAUNCH_MAX_STEPS:
             spin_for(torch, stream, 200.0)           # the GPU is busy while the host runs ahead
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(nrep + 1)]
         marks[0].record(stream)
+        nxt = reps
         for r in range(nrep):
-            graphs[(reps + r) % ngraphs].replay()
+            for _ in range(chain):
+                graphs[nxt % ngraphs].replay()
+                nxt += 1
             marks[r + 1].record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
-        return [marks[r].elapsed_time(marks[r + 1]) for r in range(nrep)]
+        return [marks[r].elapsed_time(marks[r + 1]) / chain for r in range(nrep)]
 
 
 _spin_ticks_per_us = None
@@ -140,7 +151,7 @@ def spin_for(torch, stream, microseconds):
     torch.cuda._sleep(int(max(1.0, microseconds * _spin_ticks_per_us)))
 
 
-def time_stream(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS):
+def time_stream(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS, chain=1):
     """The same measurement with plain launches instead of a graph: `steps` launches are
     enqueued behind a spin kernel long enough to cover the host's enqueue time, so that the
     GPU finds them waiting and runs them back to back between the two events.  Returns the
@@ -154,16 +165,16 @@ def time_stream(torch, launch_fn, steps, warmup, period=1, replays=MIN_REPLAYS):
             n += 1
         host_us = (time.time() - t_host) * 1e6 / n     # host cost of one enqueue
         stream.synchronize()
-        spin_for(torch, stream, 100.0 + 1.5 * host_us * steps * replays)
+        spin_for(torch, stream, 100.0 + 1.5 * host_us * steps * chain * replays)
         marks = [torch.cuda.Event(enable_timing=True) for _ in range(replays + 1)]
         marks[0].record(stream)
         for r in range(replays):
-            for i in range(steps):
-                launch_fn(r * steps + i, stream)
+            for i in range(steps * chain):
+                launch_fn(r * steps * chain + i, stream)
             marks[r + 1].record(stream)
         stream.synchronize()
         torch.cuda.synchronize()
-        return [marks[r].elapsed_time(marks[r + 1]) for r in range(replays)]
+        return [marks[r].elapsed_time(marks[r + 1]) / chain for r in range(replays)]
 
 
 def log(msg):
@@ -367,8 +378,10 @@ def main():
     # two ways of issuing the same K launches; short replays are timed with plain launches (a
     # graph replay carries a fixed begin/end cost of about 12 us that would be spread over K)
     log("%d weight sets preprocessed; timing" % nsets)
-    times_graph = time_graphs(torch, cold, args.steps, args.warmup, period=nsets)
-    times_plain = (time_stream(torch, cold, args.steps, args.warmup, period=nsets)
+    # timed regions hold at least 1000 launches: `chain` replays of `steps` launches each
+    chain = max(1, -(-1000 // args.steps))
+    times_graph = time_graphs(torch, cold, args.steps, args.warmup, period=nsets, chain=chain)
+    times_plain = (time_stream(torch, cold, args.steps, args.warmup, period=nsets, chain=chain)
                    if args.steps <= PLAIN_LAUNCH_MAX_STEPS else None)
     use_plain = times_plain is not None and median(times_plain) < median(times_graph)
     times = times_plain if use_plain else times_graph
@@ -378,8 +391,8 @@ def main():
     def timed(fn, period=1):
         """Median ms of a replay of `steps` launches of fn, issued the way the headline was."""
         if use_plain:
-            return median(time_stream(torch, fn, args.steps, args.warmup, period))
-        return median(time_graphs(torch, fn, args.steps, args.warmup, period))
+            return median(time_stream(torch, fn, args.steps, args.warmup, period, chain=chain))
+        return median(time_graphs(torch, fn, args.steps, args.warmup, period, chain=chain))
 
     kname = rsr.rsr_kernel_name(h0, rsr.RSR_BF16)
     result = {
@@ -398,15 +411,19 @@ def main():
                    "v_dtype": "bf16", "weight_sets": nsets,
                    "bytes_between_two_uses_of_a_set": (nsets - 1) * alg_bytes},
         "protocol": {"timed_with": "plain launches behind a spin kernel" if use_plain else "HIP graph replay",
-                     "timed_replays": len(times), "launches_per_replay": args.steps,
+                     "timed_regions": len(times), "replays_per_region": chain,
+                     "launches_per_replay": args.steps, "launches_per_region": chain * args.steps,
                      "statistic": "median", "us_per_step_min": min(times) * 1e3 / args.steps,
                      "us_per_step_max": max(times) * 1e3 / args.steps,
                      "graph_us_per_step": median(times_graph) * 1e3 / args.steps,
                      "plain_launch_us_per_step": (median(times_plain) * 1e3 / args.steps
                                                   if times_plain is not None else None),
-                     "note": "one replay = exactly `steps` launches back to back on one stream between two "
-                             "HIP events on that stream; consecutive replays continue the rotation over "
-                             "the weight sets; the faster of the two ways of issuing them is the value"},
+                     "note": "one replay = exactly `steps` launches back to back on one stream; a timed region "
+                             "= `replays_per_region` consecutive replays between two HIP events on that stream "
+                             "(at least 1000 launches, so that the event records do not weigh on short "
+                             "replays), its time divided by that count; consecutive replays continue the "
+                             "rotation over the weight sets; the statistic is taken over the regions; the "
+                             "faster of the two ways of issuing the launches is the value"},
     }
     achieved = alg_bytes / (us_per_step * 1e-6) / 1e9
     dense_equiv_bytes = rows * cols // 4 + cols * 2 + rows * 4
