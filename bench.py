@@ -189,8 +189,9 @@ def median(xs):
 
 
 def time_graph(torch, launch_fn, steps, warmup, period=1):
-    """Median time in ms of a replay of `steps` launches (see time_graphs)."""
-    return median(time_graphs(torch, launch_fn, steps, warmup, period))
+    """Median time in ms of a replay of `steps` launches (see time_graphs); regions of at
+    least 1000 launches."""
+    return median(time_graphs(torch, launch_fn, steps, warmup, period, chain=max(1, -(-1000 // steps))))
 
 
 def run_configs(args):
